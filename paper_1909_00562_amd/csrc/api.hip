@@ -1,0 +1,481 @@
+// C ABI of the attention-softmax library: argument checks, workspace layout
+// and the order in which the kernels of the forward / backward pass are
+// enqueued.  No arithmetic of the method lives here.
+#include "../../include/attn_softmax.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "gemm.h"
+#include "kernels.h"
+
+namespace {
+
+using namespace asx;
+
+thread_local char g_err[512] = "";
+
+as_status fail(as_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+// ---- profiling: HIP events around every launch ---------------------------------
+struct Prof {
+  bool on = false;
+  struct Rec {
+    int stage;
+    hipEvent_t a, b;
+  };
+  std::vector<Rec> pending;
+  std::vector<hipEvent_t> pool;
+  double ms[AS_STAGE_COUNT] = {0};
+  int64_t launches[AS_STAGE_COUNT] = {0};
+  hipEvent_t get() {
+    if (!pool.empty()) {
+      hipEvent_t e = pool.back();
+      pool.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Prof g_prof;
+
+struct StageTimer {
+  hipStream_t st;
+  Prof::Rec rec{0, nullptr, nullptr};
+  bool live = false;
+  StageTimer(int stage, hipStream_t s) : st(s) {
+    if (!g_prof.on) return;
+    rec.stage = stage;
+    rec.a = g_prof.get();
+    rec.b = g_prof.get();
+    if (!rec.a || !rec.b) return;
+    live = hipEventRecord(rec.a, st) == hipSuccess;
+  }
+  ~StageTimer() {
+    if (!live) return;
+    if (hipEventRecord(rec.b, st) == hipSuccess) g_prof.pending.push_back(rec);
+  }
+};
+
+// ---- workspace layout ------------------------------------------------------------
+constexpr size_t kAlign = 256;
+size_t up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+  int64_t N, ldS, ldV;
+  size_t e;  // bytes per stored element
+  size_t q, scores, alpha32, alphaE, ctx, hc, logits, lse, tokloss;
+  size_t dz, dC, dalpha, dscoreE, dQ, dbpart, partial, total;
+  // rounding remainders (value - stored(value)) of operands made inside the attention core,
+  // and the tanh derivative 1 - h_c^2 taken before h_c is rounded
+  size_t q_lo, alphaE_lo, dC_lo, dscoreE_lo, dact, dz_lo, ctx_lo;
+  int rb, nrb;
+  GemmPlan p_q, p_score, p_ctx, p_hc, p_logits, p_dwout, p_dhc, p_dwc, p_dch, p_dalpha, p_dq, p_ds, p_dwa, p_dh;
+  size_t partial_bytes;
+};
+
+bool shape_ok(const as_shape* s) {
+  if (!s) return false;
+  if (s->T < 1 || s->S < 1 || s->B < 1 || s->H < 1 || s->V < 1) return false;
+  if (s->pad_id < 0 || s->pad_id >= s->V) return false;
+  if (s->dtype != AS_F32 && s->dtype != AS_BF16) return false;
+  const int64_t N = (int64_t)s->T * s->B;
+  if (N > (1 << 30) || (int64_t)s->S * s->B > (1 << 30)) return false;
+  if ((int64_t)s->H > (1 << 20) || (int64_t)s->V > (1 << 28)) return false;
+  return true;
+}
+
+Layout make_layout(const as_shape* s) {
+  Layout L;
+  const bool bf = s->dtype == AS_BF16;
+  const int T = s->T, S = s->S, B = s->B, H = s->H, V = s->V;
+  L.N = (int64_t)T * B;
+  const int N = (int)L.N;
+  L.e = bf ? 2 : 4;
+  L.ldS = up(S, 8);
+  L.ldV = up(V, 8);
+  L.rb = xent_rows_per_block(N, V, bf);
+  L.nrb = (N + L.rb - 1) / L.rb;
+
+  L.p_q = gemm_plan(N, H, H, 1, bf, false);
+  L.p_score = gemm_plan(T, S, H, B, bf, false);
+  L.p_ctx = gemm_plan(T, H, S, B, bf, false);
+  L.p_hc = gemm_plan(N, H, 2 * H, 1, bf, false);
+  L.p_logits = gemm_plan(N, V, H, 1, bf, false);
+  L.p_dwout = gemm_plan(V, H, N, 1, bf, true);
+  L.p_dhc = gemm_plan(N, H, V, 1, bf, true);
+  L.p_dwc = gemm_plan(H, H, N, 1, bf, true);
+  L.p_dch = gemm_plan(N, H, H, 1, bf, false);
+  L.p_dalpha = gemm_plan(T, S, H, B, bf, false);
+  L.p_dq = gemm_plan(T, H, S, B, bf, false);
+  L.p_ds = gemm_plan(S, H, T, B, bf, false);
+  L.p_dwa = gemm_plan(H, H, N, 1, bf, true);
+  L.p_dh = gemm_plan(N, H, H, 1, bf, false);
+  size_t pb = 0;
+  auto mx = [&](size_t v) { if (v > pb) pb = v; };
+  mx(gemm_partial_bytes(V, H, 1, L.p_dwout.splits));
+  mx(gemm_partial_bytes(N, H, 1, L.p_dhc.splits));
+  mx(gemm_partial_bytes(H, H, 1, L.p_dwc.splits));
+  mx(gemm_partial_bytes(H, H, 1, L.p_dwa.splits));
+  L.partial_bytes = pb;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += up(bytes, kAlign);
+    return o;
+  };
+  const size_t NH = (size_t)N * H;
+  const size_t BTS = (size_t)B * T * S, BTSl = (size_t)B * T * L.ldS;
+  L.q = take(NH * L.e);
+  L.scores = take(BTS * 4);
+  L.alpha32 = take(BTS * 4);
+  L.alphaE = take(BTSl * L.e);
+  L.ctx = take(NH * L.e);
+  L.hc = take(NH * L.e);
+  L.logits = take((size_t)N * L.ldV * L.e);
+  L.lse = take((size_t)N * 4);
+  L.tokloss = take((size_t)N * 4);
+  L.dz = take(NH * L.e);
+  L.dC = take(NH * L.e);
+  L.dalpha = take(BTS * 4);
+  L.dscoreE = take(BTSl * L.e);
+  L.dQ = take(NH * L.e);
+  L.dbpart = take((size_t)L.nrb * V * 4);
+  L.partial = take(pb);
+  L.q_lo = take(NH * L.e);
+  L.alphaE_lo = take(BTSl * L.e);
+  L.dC_lo = take(NH * L.e);
+  L.dscoreE_lo = take(BTSl * L.e);
+  L.dact = take(NH * 4);
+  L.ctx_lo = take(NH * L.e);
+  L.dz_lo = take(NH * L.e);
+  L.total = off;
+  return L;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+as_status check_common(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                       const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                       const int32_t* targets, void* ws, size_t ws_bytes, Layout* L) {
+  if (!s) return fail(AS_ERR_NULL, "shape is NULL");
+  if (s->dtype != AS_F32 && s->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", s->dtype);
+  if (!shape_ok(s))
+    return fail(AS_ERR_SHAPE, "bad shape T=%d S=%d B=%d H=%d V=%d pad_id=%d", s->T, s->S, s->B, s->H, s->V,
+                s->pad_id);
+  if (!h_dec || !h_enc || !src_len || !W_a || !W_c || !W_out || !b_out || !targets || !ws)
+    return fail(AS_ERR_NULL, "a required pointer is NULL");
+  if (s->dtype == AS_BF16 && (s->H % 8) != 0) return fail(AS_ERR_ALIGN, "AS_BF16 needs H %% 8 == 0 (H=%d)", s->H);
+  const void* ptrs[] = {h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, ws};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return fail(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  *L = make_layout(s);
+  if (ws_bytes < L->total)
+    return fail(AS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
+  return AS_OK;
+}
+
+#define AS_TRY(stage, expr)                                                              \
+  do {                                                                                   \
+    hipError_t e_;                                                                       \
+    {                                                                                    \
+      StageTimer timer_(stage, st);                                                      \
+      e_ = (expr);                                                                       \
+    }                                                                                    \
+    if (e_ != hipSuccess) return fail(AS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t attn_softmax_workspace_bytes(const as_shape* shape) {
+  if (!shape_ok(shape)) return 0;
+  if (shape->dtype == AS_BF16 && (shape->H % 8) != 0) return 0;
+  return make_layout(shape).total;
+}
+
+const char* attn_softmax_last_error(void) { return g_err; }
+
+as_status attn_softmax_view(const as_shape* shape, void* workspace, int which, void** ptr, size_t* bytes,
+                            int64_t* row_stride) {
+  if (!shape || !workspace || !ptr || !bytes) return fail(AS_ERR_NULL, "a required pointer is NULL");
+  if (shape->dtype != AS_F32 && shape->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", shape->dtype);
+  if (!shape_ok(shape)) return fail(AS_ERR_SHAPE, "bad shape");
+  if (shape->dtype == AS_BF16 && (shape->H % 8) != 0) return fail(AS_ERR_ALIGN, "AS_BF16 needs H %% 8 == 0");
+  const Layout L = make_layout(shape);
+  char* w = reinterpret_cast<char*>(workspace);
+  const size_t NH = (size_t)L.N * shape->H;
+  int64_t ld = 0;
+  switch (which) {
+    case AS_VIEW_ALPHA: *ptr = w + L.alpha32; *bytes = (size_t)shape->B * shape->T * shape->S * 4; ld = shape->S; break;
+    case AS_VIEW_CTX: *ptr = w + L.ctx; *bytes = NH * L.e; ld = shape->H; break;
+    case AS_VIEW_HC: *ptr = w + L.hc; *bytes = NH * L.e; ld = shape->H; break;
+    case AS_VIEW_LOGITS: *ptr = w + L.logits; *bytes = (size_t)L.N * L.ldV * L.e; ld = L.ldV; break;
+    case AS_VIEW_LSE: *ptr = w + L.lse; *bytes = (size_t)L.N * 4; ld = shape->B; break;
+    default: return fail(AS_ERR_SHAPE, "unknown view %d", which);
+  }
+  if (row_stride) *row_stride = ld;
+  return AS_OK;
+}
+
+as_status attn_softmax_fwd(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                           const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                           const int32_t* targets, float* loss_sum, int32_t* n_tok, float* tok_loss,
+                           int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  Layout L;
+  as_status rc = check_common(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, workspace,
+                              workspace_bytes, &L);
+  if (rc != AS_OK) return rc;
+  if (!loss_sum || !n_tok) return fail(AS_ERR_NULL, "loss_sum / n_tok is NULL");
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const bool bf = s->dtype == AS_BF16;
+  const int T = s->T, S = s->S, B = s->B, H = s->H, V = s->V, N = (int)L.N;
+  char* w = reinterpret_cast<char*>(workspace);
+  const char* hd = reinterpret_cast<const char*>(h_dec);
+  const char* he = reinterpret_cast<const char*>(h_enc);
+  const char* wc = reinterpret_cast<const char*>(W_c);
+  const int64_t BH = (int64_t)B * H;
+
+  {  // Q = h_dec W_a                                                    (Eq. 2)
+    GemmArgs g;
+    g.seg(hd, H, 0, W_a, H, 0, H);
+    g.a_kc = true; g.b_kc = false;
+    g.M = N; g.N = H;
+    g.C = w + L.q; g.ldc = H; g.c_bf16 = bf;
+    g.C_lo = w + L.q_lo;
+    AS_TRY(AS_STAGE_GEMM_Q, launch_gemm(g, bf, L.p_q.big_tile, st));
+  }
+  {  // score[b] = Q_b h_enc_b^T, one product per sentence                  (Eq. 2)
+    GemmArgs g;
+    g.seg(w + L.q, BH, H, he, BH, H, H);
+    g.seg(w + L.q_lo, BH, H, he, BH, H, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = T; g.N = S; g.batch = B;
+    g.C = w + L.scores; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
+    AS_TRY(AS_STAGE_ATTN_SCORE, launch_gemm(g, bf, L.p_score.big_tile, st));
+  }
+  AS_TRY(AS_STAGE_ATTN_SOFTMAX,                                        // Eq. 1
+         launch_attn_softmax_rows(reinterpret_cast<const float*>(w + L.scores), src_len, B, T, S,
+                                  reinterpret_cast<float*>(w + L.alpha32), w + L.alphaE,
+                                  w + L.alphaE_lo, L.ldS, bf, attn_mask, st));
+  {  // ctx_b = alpha_b h_enc_b                                            (Eq. 3)
+    GemmArgs g;
+    g.seg(w + L.alphaE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+    g.seg(w + L.alphaE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+    g.a_kc = true; g.b_kc = false;
+    g.M = T; g.N = H; g.batch = B;
+    g.C = w + L.ctx; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
+    g.C_lo = w + L.ctx_lo;
+    AS_TRY(AS_STAGE_ATTN_CTX, launch_gemm(g, bf, L.p_ctx.big_tile, st));
+  }
+  {  // h_c = tanh(W_c[:, :H] ctx + W_c[:, H:] h_dec)                       (Eq. 4)
+    GemmArgs g;
+    g.seg(w + L.ctx, H, 0, wc, 2 * H, 0, H);
+    g.seg(w + L.ctx_lo, H, 0, wc, 2 * H, 0, H);
+    g.seg(hd, H, 0, wc + (size_t)H * L.e, 2 * H, 0, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = N; g.N = H; g.act_tanh = 1;
+    g.C = w + L.hc; g.ldc = H; g.c_bf16 = bf;
+    g.C_dact = reinterpret_cast<float*>(w + L.dact);
+    AS_TRY(AS_STAGE_GEMM_HC, launch_gemm(g, bf, L.p_hc.big_tile, st));
+  }
+  {  // logits = h_c W_out^T + b_out                                        (Eq. 5)
+    GemmArgs g;
+    g.seg(w + L.hc, H, 0, W_out, H, 0, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = N; g.N = V; g.bias = b_out;
+    g.C = w + L.logits; g.ldc = L.ldV; g.c_bf16 = bf;
+    AS_TRY(AS_STAGE_GEMM_LOGITS, launch_gemm(g, bf, L.p_logits.big_tile, st));
+  }
+  AS_TRY(AS_STAGE_XENT_STATS,                                          // Eq. 5-6
+         launch_xent_stats(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id, reinterpret_cast<float*>(w + L.lse),
+                           reinterpret_cast<float*>(w + L.tokloss), tok_loss, argmax, tgt_mask, st));
+  AS_TRY(AS_STAGE_MISC, launch_loss_reduce(reinterpret_cast<const float*>(w + L.tokloss), targets, N, V, s->pad_id,
+                                           loss_sum, n_tok, st));
+  return AS_OK;
+}
+
+as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                           const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                           const int32_t* targets, void* workspace, size_t workspace_bytes, float* d_h_dec,
+                           float* d_h_enc, float* dW_a, float* dW_c, float* dW_out, float* db_out,
+                           void* hip_stream) {
+  Layout L;
+  as_status rc = check_common(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, workspace,
+                              workspace_bytes, &L);
+  if (rc != AS_OK) return rc;
+  if (!d_h_dec || !d_h_enc || !dW_a || !dW_c || !dW_out || !db_out)
+    return fail(AS_ERR_NULL, "a gradient output pointer is NULL");
+  const void* outs[] = {d_h_dec, d_h_enc, dW_a, dW_c, dW_out, db_out};
+  for (const void* p : outs)
+    if (!aligned16(p)) return fail(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const bool bf = s->dtype == AS_BF16;
+  const int T = s->T, S = s->S, B = s->B, H = s->H, V = s->V, N = (int)L.N;
+  char* w = reinterpret_cast<char*>(workspace);
+  const char* hd = reinterpret_cast<const char*>(h_dec);
+  const char* he = reinterpret_cast<const char*>(h_enc);
+  const char* wc = reinterpret_cast<const char*>(W_c);
+  const int64_t BH = (int64_t)B * H;
+  float* partial = reinterpret_cast<float*>(w + L.partial);
+
+  // dlogits = g (softmax - onehot) in place; db_out = column sums
+  AS_TRY(AS_STAGE_XENT_DLOGITS,
+         launch_xent_dlogits(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id,
+                             reinterpret_cast<const float*>(w + L.lse), s->grad_scale,
+                             reinterpret_cast<float*>(w + L.dbpart), st));
+  AS_TRY(AS_STAGE_MISC, launch_db_reduce(reinterpret_cast<const float*>(w + L.dbpart), L.nrb, V, db_out, st));
+  {  // dW_out = dlogits^T h_c
+    GemmArgs g;
+    g.seg(w + L.logits, L.ldV, 0, w + L.hc, H, 0, N);
+    g.a_kc = false; g.b_kc = false;
+    g.M = V; g.N = H;
+    g.C = dW_out; g.ldc = H; g.c_bf16 = false;
+    g.splits = L.p_dwout.splits; g.partial = partial;
+    AS_TRY(AS_STAGE_GEMM_DWOUT, launch_gemm(g, bf, L.p_dwout.big_tile, st));
+  }
+  {  // dz = (dlogits W_out) * (1 - h_c^2), the factor saved by the forward pass
+    GemmArgs g;
+    g.seg(w + L.logits, L.ldV, 0, W_out, H, 0, V);
+    g.a_kc = true; g.b_kc = false;
+    g.M = N; g.N = H;
+    g.gate = reinterpret_cast<const float*>(w + L.dact); g.ldg = H;
+    g.C = w + L.dz; g.ldc = H; g.c_bf16 = bf;
+    g.C_lo = w + L.dz_lo;
+    g.splits = L.p_dhc.splits; g.partial = partial;
+    AS_TRY(AS_STAGE_GEMM_DHC, launch_gemm(g, bf, L.p_dhc.big_tile, st));
+  }
+  for (int half = 0; half < 2; ++half) {  // dW_c = dz^T [ctx ; h_dec]
+    GemmArgs g;
+    g.seg(w + L.dz, H, 0, half == 0 ? (const void*)(w + L.ctx) : (const void*)hd, H, 0, N);
+    g.a_kc = false; g.b_kc = false;
+    g.M = H; g.N = H;
+    g.C = dW_c + (size_t)half * H; g.ldc = 2 * H; g.c_bf16 = false;
+    g.splits = L.p_dwc.splits; g.partial = partial;
+    AS_TRY(AS_STAGE_GEMM_DWC, launch_gemm(g, bf, L.p_dwc.big_tile, st));
+  }
+  {  // dC = dz W_c[:, :H]
+    GemmArgs g;
+    g.seg(w + L.dz, H, 0, wc, 2 * H, 0, H);
+    g.seg(w + L.dz_lo, H, 0, wc, 2 * H, 0, H);
+    g.a_kc = true; g.b_kc = false;
+    g.M = N; g.N = H;
+    g.C = w + L.dC; g.ldc = H; g.c_bf16 = bf;
+    g.C_lo = w + L.dC_lo;
+    AS_TRY(AS_STAGE_GEMM_DCH, launch_gemm(g, bf, L.p_dch.big_tile, st));
+  }
+  {  // dH1 = dz W_c[:, H:]  -> d_h_dec
+    GemmArgs g;
+    g.seg(w + L.dz, H, 0, wc + (size_t)H * L.e, 2 * H, 0, H);
+    g.a_kc = true; g.b_kc = false;
+    g.M = N; g.N = H;
+    g.C = d_h_dec; g.ldc = H; g.c_bf16 = false;
+    AS_TRY(AS_STAGE_GEMM_DCH, launch_gemm(g, bf, L.p_dch.big_tile, st));
+  }
+  {  // dalpha_b = dC_b h_enc_b^T
+    GemmArgs g;
+    g.seg(w + L.dC, BH, H, he, BH, H, H);
+    g.seg(w + L.dC_lo, BH, H, he, BH, H, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = T; g.N = S; g.batch = B;
+    g.C = w + L.dalpha; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
+    AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dalpha.big_tile, st));
+  }
+  AS_TRY(AS_STAGE_ATTN_SOFTMAX_BWD,
+         launch_attn_softmax_rows_bwd(reinterpret_cast<const float*>(w + L.alpha32),
+                                      reinterpret_cast<const float*>(w + L.dalpha), B, T, S, w + L.dscoreE,
+                                      w + L.dscoreE_lo, L.ldS, bf, st));
+  {  // dQ_b = dscore_b h_enc_b
+    GemmArgs g;
+    g.seg(w + L.dscoreE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+    g.seg(w + L.dscoreE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+    g.a_kc = true; g.b_kc = false;
+    g.M = T; g.N = H; g.batch = B;
+    g.C = w + L.dQ; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
+    AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dq.big_tile, st));
+  }
+  {  // d_h_enc_b = alpha_b^T dC_b + dscore_b^T Q_b  (rows s >= src_len[b]: alpha = dscore = 0)
+    GemmArgs g;
+    const int64_t sAl = (int64_t)T * L.ldS;
+    g.seg(w + L.alphaE, L.ldS, sAl, w + L.dC, BH, H, T);
+    g.seg(w + L.dscoreE, L.ldS, sAl, w + L.q, BH, H, T);
+    // first-order remainder terms of the two products
+    g.seg(w + L.alphaE_lo, L.ldS, sAl, w + L.dC, BH, H, T);
+    g.seg(w + L.alphaE, L.ldS, sAl, w + L.dC_lo, BH, H, T);
+    g.seg(w + L.dscoreE_lo, L.ldS, sAl, w + L.q, BH, H, T);
+    g.seg(w + L.dscoreE, L.ldS, sAl, w + L.q_lo, BH, H, T);
+    g.a_kc = false; g.b_kc = false;
+    g.M = S; g.N = H; g.batch = B;
+    g.C = d_h_enc; g.ldc = BH; g.sC = H; g.c_bf16 = false;
+    AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_ds.big_tile, st));
+  }
+  {  // dW_a = h_dec^T dQ
+    GemmArgs g;
+    g.seg(hd, H, 0, w + L.dQ, H, 0, N);
+    g.a_kc = false; g.b_kc = false;
+    g.M = H; g.N = H;
+    g.C = dW_a; g.ldc = H; g.c_bf16 = false;
+    g.splits = L.p_dwa.splits; g.partial = partial;
+    AS_TRY(AS_STAGE_GEMM_DWA, launch_gemm(g, bf, L.p_dwa.big_tile, st));
+  }
+  {  // d_h_dec += dQ W_a^T
+    GemmArgs g;
+    g.seg(w + L.dQ, H, 0, W_a, H, 0, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = N; g.N = H;
+    g.C = d_h_dec; g.ldc = H; g.c_bf16 = false; g.accumulate = 1;
+    AS_TRY(AS_STAGE_GEMM_DH, launch_gemm(g, bf, L.p_dh.big_tile, st));
+  }
+  return AS_OK;
+}
+
+as_status attn_softmax_profile_enable(int enable) {
+  // drop whatever is pending
+  for (auto& r : g_prof.pending) {
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.pending.clear();
+  for (int i = 0; i < AS_STAGE_COUNT; ++i) {
+    g_prof.ms[i] = 0;
+    g_prof.launches[i] = 0;
+  }
+  g_prof.on = enable != 0;
+  return AS_OK;
+}
+
+as_status attn_softmax_profile_read(double* ms_total, int64_t* launches) {
+  for (auto& r : g_prof.pending) {
+    hipError_t e = hipEventSynchronize(r.b);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e != hipSuccess) return fail(AS_ERR_HIP, "profile events: %s", hipGetErrorString(e));
+    g_prof.ms[r.stage] += ms;
+    g_prof.launches[r.stage] += 1;
+    g_prof.pool.push_back(r.a);
+    g_prof.pool.push_back(r.b);
+  }
+  g_prof.pending.clear();
+  for (int i = 0; i < AS_STAGE_COUNT; ++i) {
+    if (ms_total) ms_total[i] = g_prof.ms[i];
+    if (launches) launches[i] = g_prof.launches[i];
+  }
+  return AS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Host-side description of one (optionally batched, optionally multi-segment)
+// matrix product  C[m,n] = epilogue( sum_seg sum_k A_seg(m,k) * B_seg(n,k) ).
+// Segments let one launch add several products into the same accumulators:
+// the two halves of W_c [c ; h], or the high and low bf16 parts of an operand
+// that was produced inside the path and must not lose its fp32 precision.
+//
+// Operand addressing (elements of the storage type):
+//   a_kc : A(m,k) = A[m*lda + k]   (reduction index contiguous)
+//   !a_kc: A(m,k) = A[k*lda + m]   (stored transposed: row index = k)
+//   b_kc : B(n,k) = B[n*ldb + k]
+//   !b_kc: B(n,k) = B[k*ldb + n]
+// The bf16 kernels read 16-byte vectors along the contiguous index, so for a
+// bf16 operand: base pointers and batch strides are 16-byte aligned, ld % 8 == 0,
+// the allocation extends to a multiple of 8 along the contiguous index, and when
+// the reduction index is the contiguous one and K % 8 != 0 the padding elements
+// up to the next multiple of 8 must be zero.  The fp32 kernel has no such needs.
+//
+// Epilogue, applied in this order:  v = acc; v += bias[n]; v = tanh(v) if act;
+// v *= gate[m,n] if gate; v += C_old[m,n] if accumulate (fp32 C only);
+// C[m,n] = v rounded to the output type.  Optional second outputs with C's
+// layout:  C_lo[m,n] = v - C[m,n] (type of C), the part of v the rounding lost;
+// C_dact[m,n] = 1 - v^2 as float (the tanh derivative, taken before v is rounded).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asx {
+
+constexpr int kMaxSeg = 6;
+
+struct GemmArgs {
+  const void* A[kMaxSeg] = {};
+  const void* B[kMaxSeg] = {};
+  int64_t lda[kMaxSeg] = {}, ldb[kMaxSeg] = {};
+  int64_t sA[kMaxSeg] = {}, sB[kMaxSeg] = {};  // batch strides
+  int K[kMaxSeg] = {};                         // K[s] = 0: segment unused
+  int nseg = 0;
+  void seg(const void* a, int64_t lda_, int64_t sa_, const void* b, int64_t ldb_, int64_t sb_, int k) {
+    A[nseg] = a; lda[nseg] = lda_; sA[nseg] = sa_;
+    B[nseg] = b; ldb[nseg] = ldb_; sB[nseg] = sb_;
+    K[nseg] = k; ++nseg;
+  }
+  bool a_kc = true, b_kc = true;
+  int M = 0, N = 0;
+  void* C = nullptr;
+  int64_t ldc = 0, sC = 0;
+  bool c_bf16 = false;          // output storage: bf16 bits or float
+  void* C_lo = nullptr;         // optional rounding remainder of C
+  float* C_dact = nullptr;      // optional 1 - v^2 (float)
+  const void* bias = nullptr;   // [N], storage type of the inputs
+  const float* gate = nullptr;  // [M,ldg] multiplier (float)
+  int64_t ldg = 0;
+  int act_tanh = 0;
+  int accumulate = 0;
+  int batch = 1;
+  int splits = 1;               // split of the reduction index (single segment only)
+  float* partial = nullptr;     // [batch*splits, M, N] floats when splits > 1
+};
+
+// Tile plan shared by workspace sizing and launching.
+struct GemmPlan {
+  int big_tile;   // bf16: 1 = 256x256 block tile, 0 = 128x128
+  int splits;
+};
+GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split);
+inline size_t gemm_partial_bytes(int M, int N, int batch, int splits) {
+  return splits > 1 ? (size_t)splits * batch * M * N * sizeof(float) : 0;
+}
+
+// Enqueue; return hipSuccess or the launch error.  `in_bf16` selects the kernel family.
+hipError_t launch_gemm(const GemmArgs& g, bool in_bf16, int big_tile, hipStream_t st);
+hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st);
+hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st);
+// partial[batch*splits][M][N] -> C with the epilogue of g
+hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st);
+
+}  // namespace asx

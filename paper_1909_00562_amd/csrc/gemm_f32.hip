@@ -1,0 +1,240 @@
+// fp32 matrix products for the AS_F32 path (fp32 operands, products summed in
+// fp64 so that each output is rounded once; plain FMA arithmetic, LDS tiled),
+// the split-K combine kernel shared with the bf16 path, and the tile planner.
+#include "common.h"
+#include "gemm.h"
+
+namespace asx {
+
+struct GemmDevF {
+  const float* A[kMaxSeg];
+  const float* B[kMaxSeg];
+  int64_t sam[kMaxSeg], sak[kMaxSeg], sbn[kMaxSeg], sbk[kMaxSeg];  // element strides of A(m,k), B(n,k)
+  int64_t sA[kMaxSeg], sB[kMaxSeg];
+  int K[kMaxSeg];
+  int M, N;
+  float* C;
+  float* C_lo;
+  float* C_dact;
+  int64_t ldc, sC;
+  const float* bias;
+  const float* gate;
+  int64_t ldg;
+  int act_tanh, accumulate;
+  int splits;
+  float* partial;
+  int kper;
+  int a_kc, b_kc;
+};
+
+constexpr int FT = 64;   // block tile edge
+constexpr int FK = 16;   // reduction slice
+
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
+  __shared__ float As[FK][FT + 4];
+  __shared__ float Bs[FK][FT + 4];
+  const int tid = threadIdx.x;
+  const int tx = tid & 15, ty = tid >> 4;
+  const int m0 = blockIdx.y * FT, n0 = blockIdx.x * FT;
+  const int z = blockIdx.z;
+  const int batch = z / p.splits, split = z - batch * p.splits;
+
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+
+  for (int seg = 0; seg < kMaxSeg; ++seg) {
+    if (p.K[seg] <= 0) continue;
+    int kbeg = 0, kend = p.K[seg];
+    if (p.splits > 1) {
+      kbeg = split * p.kper;
+      kend = kbeg + p.kper < kend ? kbeg + p.kper : kend;
+    }
+    const float* A = p.A[seg] + (int64_t)batch * p.sA[seg];
+    const float* B = p.B[seg] + (int64_t)batch * p.sB[seg];
+    for (int k0 = kbeg; k0 < kend; k0 += FK) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int idx = tid + 256 * j;
+        int m, k;
+        if (p.a_kc) { k = idx & 15; m = idx >> 4; } else { m = idx & 63; k = idx >> 6; }
+        const int gm = m0 + m, gk = k0 + k;
+        As[k][m] = (gm < p.M && gk < kend) ? A[(int64_t)gm * p.sam[seg] + (int64_t)gk * p.sak[seg]] : 0.f;
+        int n;
+        if (p.b_kc) { k = idx & 15; n = idx >> 4; } else { n = idx & 63; k = idx >> 6; }
+        const int gn = n0 + n;
+        const int gk2 = k0 + k;
+        Bs[k][n] = (gn < p.N && gk2 < kend) ? B[(int64_t)gn * p.sbn[seg] + (int64_t)gk2 * p.sbk[seg]] : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < FK; ++k) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fma((double)a[i], (double)b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = m0 + ty * 4 + i;
+    if (row >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx * 4 + j;
+      if (col >= p.N) continue;
+      double v = acc[i][j];
+      if (p.splits > 1) {
+        p.partial[((int64_t)z * p.M + row) * p.N + col] = (float)v;
+        continue;
+      }
+      if (p.bias) v += (double)p.bias[col];
+      if (p.act_tanh) v = tanh(v);
+      if (p.gate) v *= (double)p.gate[(int64_t)row * p.ldg + col];
+      const int64_t ci = (int64_t)batch * p.sC + (int64_t)row * p.ldc + col;
+      if (p.accumulate) v += (double)p.C[ci];
+      const float vf = (float)v;
+      p.C[ci] = vf;
+      if (p.C_lo) p.C_lo[ci] = (float)(v - (double)vf);
+      if (p.C_dact) p.C_dact[ci] = (float)(1.0 - v * v);
+    }
+  }
+}
+
+hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st) {
+  if (g.M < 1 || g.N < 1 || g.batch < 1 || g.splits < 1 || g.c_bf16) return hipErrorInvalidValue;
+  if (g.splits > 1 && (g.K[1] != 0 || g.partial == nullptr)) return hipErrorInvalidValue;
+  if (g.splits > 1 && g.C_dact) return hipErrorInvalidValue;
+  GemmDevF d;
+  for (int s = 0; s < kMaxSeg; ++s) {
+    d.A[s] = reinterpret_cast<const float*>(g.A[s]);
+    d.B[s] = reinterpret_cast<const float*>(g.B[s]);
+    d.sam[s] = g.a_kc ? g.lda[s] : 1;
+    d.sak[s] = g.a_kc ? 1 : g.lda[s];
+    d.sbn[s] = g.b_kc ? g.ldb[s] : 1;
+    d.sbk[s] = g.b_kc ? 1 : g.ldb[s];
+    d.sA[s] = g.sA[s];
+    d.sB[s] = g.sB[s];
+    d.K[s] = g.K[s];
+  }
+  d.M = g.M;
+  d.N = g.N;
+  d.C = reinterpret_cast<float*>(g.C);
+  d.C_lo = reinterpret_cast<float*>(g.C_lo);
+  d.C_dact = g.C_dact;
+  d.ldc = g.ldc;
+  d.sC = g.sC;
+  d.bias = reinterpret_cast<const float*>(g.bias);
+  d.gate = g.gate;
+  d.ldg = g.ldg;
+  d.act_tanh = g.act_tanh;
+  d.accumulate = g.accumulate;
+  d.splits = g.splits;
+  d.partial = g.partial;
+  d.a_kc = g.a_kc;
+  d.b_kc = g.b_kc;
+  const int ktiles = (g.K[0] + FK - 1) / FK;
+  d.kper = ((ktiles + g.splits - 1) / g.splits) * FK;
+  if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
+  dim3 grid((g.N + FT - 1) / FT, (g.M + FT - 1) / FT, g.batch * g.splits);
+  hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, st, d);
+  return hipGetLastError();
+}
+
+// ---- split-K combine: C = epilogue(sum_s partial[b*splits+s]) in fixed order --
+template <typename TIn, bool OUT_BF16>
+__global__ __launch_bounds__(256) void splitk_combine_kernel(const float* __restrict__ partial, int splits,
+                                                            int M, int N, void* C, void* C_lo, int64_t ldc,
+                                                            int64_t sC, const TIn* bias, const float* gate,
+                                                            int64_t ldg, int act_tanh, int accumulate) {
+  const int64_t mn = (int64_t)M * N;
+  const int batch = blockIdx.y;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn; i += (int64_t)gridDim.x * 256) {
+    const int row = (int)(i / N), col = (int)(i - (int64_t)row * N);
+    const float* P = partial + (int64_t)batch * splits * mn + i;
+    float v = 0.f;
+    for (int s = 0; s < splits; ++s) v += P[(int64_t)s * mn];
+    if (bias) v += ld_elem<TIn>(bias, col);
+    if (act_tanh) v = tanhf(v);
+    if (gate) v *= gate[(int64_t)row * ldg + col];
+    const int64_t ci = (int64_t)batch * sC + (int64_t)row * ldc + col;
+    if constexpr (OUT_BF16) {
+      const uint32_t hi = f32_to_bf16_bits(v);
+      reinterpret_cast<uint16_t*>(C)[ci] = (uint16_t)hi;
+      if (C_lo) reinterpret_cast<uint16_t*>(C_lo)[ci] = (uint16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
+    } else {
+      float* Cf = reinterpret_cast<float*>(C);
+      if (accumulate) v += Cf[ci];
+      Cf[ci] = v;
+      if (C_lo) reinterpret_cast<float*>(C_lo)[ci] = 0.f;   // partial sums were already rounded to fp32
+    }
+  }
+}
+
+hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st) {
+  const int64_t mn = (int64_t)g.M * g.N;
+  int blocks = (int)((mn + 255) / 256);
+  if (blocks > 8192) blocks = 8192;
+  dim3 grid(blocks, g.batch);
+  if (in_bf16) {
+    const uint16_t* bias = reinterpret_cast<const uint16_t*>(g.bias);
+    const float* gate = g.gate;
+    if (g.c_bf16)
+      hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, true>), grid, dim3(256), 0, st, g.partial, g.splits,
+                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate);
+    else
+      hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, false>), grid, dim3(256), 0, st, g.partial, g.splits,
+                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate);
+  } else {
+    hipLaunchKernelGGL((splitk_combine_kernel<float, false>), grid, dim3(256), 0, st, g.partial, g.splits, g.M,
+                       g.N, g.C, g.C_lo, g.ldc, g.sC, reinterpret_cast<const float*>(g.bias),
+                       g.gate, g.ldg, g.act_tanh, g.accumulate);
+  }
+  return hipGetLastError();
+}
+
+// ---- planner ----------------------------------------------------------------
+GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split) {
+  GemmPlan pl;
+  pl.big_tile = 0;
+  pl.splits = 1;
+  const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256) * batch;
+  const int edge = bf16 ? 128 : FT;
+  const int kt = bf16 ? 64 : FK;
+  int64_t tiles = (int64_t)((M + edge - 1) / edge) * ((N + edge - 1) / edge) * batch;
+  if (bf16 && t256 >= 512) {
+    pl.big_tile = 1;
+    return pl;
+  }
+  if (allow_split && tiles < 384) {
+    const int ktiles = (K + kt - 1) / kt;
+    int64_t want = (768 + tiles - 1) / tiles;
+    int64_t cap = ktiles / 4;            // at least 4 reduction tiles per split
+    if (want > cap) want = cap;
+    if (want > 32) want = 32;
+    if (want > 1) {
+      const int per = (int)((ktiles + want - 1) / want);
+      pl.splits = (ktiles + per - 1) / per;   // no empty split
+    }
+  }
+  return pl;
+}
+
+hipError_t launch_gemm(const GemmArgs& g, bool in_bf16, int big_tile, hipStream_t st) {
+  hipError_t e = in_bf16 ? launch_gemm_bf16(g, big_tile, st) : launch_gemm_f32(g, st);
+  if (e != hipSuccess) return e;
+  if (g.splits > 1) e = launch_splitk_combine(g, in_bf16, st);
+  return e;
+}
+
+}  // namespace asx

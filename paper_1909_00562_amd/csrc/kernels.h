@@ -1,0 +1,39 @@
+// Launchers of the row-wise kernels (masked attention softmax, vocabulary
+// softmax cross-entropy).  All enqueue on `st` and return the launch status.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace asx {
+
+// Eq. 1: alpha[b,t,:] = softmax(score[b,t,:]) over s < clamp(src_len[b],0,S),
+// exactly 0 elsewhere.  Writes alpha32 [B,T,S], a copy in the storage type
+// alphaE [B,T,ldS] (columns S..ldS-1 zero), if non-null the rounding remainder
+// alphaE_lo = alpha - alphaE in the storage type, and, if non-null, attn_mask [B,S].
+hipError_t launch_attn_softmax_rows(const float* score, const int32_t* src_len, int B, int T, int S,
+                                    float* alpha32, void* alphaE, void* alphaE_lo, int64_t ldS, bool e_bf16,
+                                    uint8_t* attn_mask, hipStream_t st);
+// Softmax Jacobian: dscore = alpha * (dalpha - sum_s alpha*dalpha), storage type, [B,T,ldS] zero
+// padded; dscoreE_lo (optional) receives the rounding remainder.
+hipError_t launch_attn_softmax_rows_bwd(const float* alpha32, const float* dalpha, int B, int T, int S,
+                                        void* dscoreE, void* dscoreE_lo, int64_t ldS, bool e_bf16,
+                                        hipStream_t st);
+
+// Eq. 5-6 per row n of logits [N,ldV]: lse, loss, argmax, target mask.
+hipError_t launch_xent_stats(const void* logits, int64_t ldV, bool e_bf16, int N, int V,
+                             const int32_t* targets, int pad_id, float* lse, float* tok_loss_ws,
+                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, hipStream_t st);
+// loss_sum = sum(tok_loss_ws) in double, n_tok = number of non-pad targets; fixed order.
+hipError_t launch_loss_reduce(const float* tok_loss_ws, const int32_t* targets, int N, int V, int pad_id,
+                              float* loss_sum, int32_t* n_tok, hipStream_t st);
+
+// rows of logits handled by one block of the dlogits kernel (also sizes db_partial)
+int xent_rows_per_block(int N, int V, bool e_bf16);
+// dlogits = g * (exp(logit - lse) - onehot) on non-pad rows, 0 on pad rows and on
+// columns V..ldV-1, in place; db_partial[rb][v] = column sums of row block rb.
+hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, int V, const int32_t* targets,
+                               int pad_id, const float* lse, float g, float* db_partial, hipStream_t st);
+// db_out[v] = sum_rb db_partial[rb][v]
+hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st);
+
+}  // namespace asx

@@ -1,0 +1,247 @@
+// Vocabulary softmax cross-entropy (Eq. 5-6 of section 3.2) without ever
+// forming the probability matrix: a streaming statistics pass (online max /
+// sum-exp, target logit, argmax) and an in-place pass that turns the stored
+// logits into dlogits = g*(p - onehot) while summing the columns for db_out.
+// Both passes are pure HBM streams: 16-byte loads/stores, fp32 arithmetic.
+#include "common.h"
+#include "kernels.h"
+
+namespace asx {
+
+template <typename TE> struct Vec;
+template <> struct Vec<uint16_t> { static constexpr int N = 8; };
+template <> struct Vec<float> { static constexpr int N = 4; };
+
+template <typename TE>
+__device__ __forceinline__ void unpack(const uint4& q, float (&f)[Vec<TE>::N]) {
+  if constexpr (sizeof(TE) == 2) {
+    f[0] = lo_bf16(q.x); f[1] = hi_bf16(q.x); f[2] = lo_bf16(q.y); f[3] = hi_bf16(q.y);
+    f[4] = lo_bf16(q.z); f[5] = hi_bf16(q.z); f[6] = lo_bf16(q.w); f[7] = hi_bf16(q.w);
+  } else {
+    f[0] = __builtin_bit_cast(float, q.x); f[1] = __builtin_bit_cast(float, q.y);
+    f[2] = __builtin_bit_cast(float, q.z); f[3] = __builtin_bit_cast(float, q.w);
+  }
+}
+template <typename TE>
+__device__ __forceinline__ uint4 pack(const float (&f)[Vec<TE>::N]) {
+  uint4 q;
+  if constexpr (sizeof(TE) == 2) {
+    q.x = pack_bf16(f[0], f[1]); q.y = pack_bf16(f[2], f[3]);
+    q.z = pack_bf16(f[4], f[5]); q.w = pack_bf16(f[6], f[7]);
+  } else {
+    q.x = __builtin_bit_cast(uint32_t, f[0]); q.y = __builtin_bit_cast(uint32_t, f[1]);
+    q.z = __builtin_bit_cast(uint32_t, f[2]); q.w = __builtin_bit_cast(uint32_t, f[3]);
+  }
+  return q;
+}
+
+// running (max, sum of exp relative to max, lowest index of the max)
+struct RowStat {
+  float m, s;
+  int idx;
+};
+__device__ __forceinline__ RowStat combine(const RowStat& a, const RowStat& b) {
+  RowStat r;
+  r.m = fmaxf(a.m, b.m);
+  const float sa = a.m == r.m ? 1.f : __expf(a.m - r.m);
+  const float sb = b.m == r.m ? 1.f : __expf(b.m - r.m);
+  r.s = a.s * sa + b.s * sb;
+  r.idx = a.m > b.m ? a.idx : (b.m > a.m ? b.idx : (a.idx < b.idx ? a.idx : b.idx));
+  return r;
+}
+
+template <typename TE>
+__global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ logits, int64_t ldV, int V,
+                                                        const int32_t* __restrict__ targets, int pad_id,
+                                                        float* __restrict__ lse, float* __restrict__ tok_loss_ws,
+                                                        float* __restrict__ tok_loss, int32_t* __restrict__ argmax,
+                                                        uint8_t* __restrict__ tgt_mask) {
+  constexpr int VEC = Vec<TE>::N;
+  const int n = blockIdx.x, tid = threadIdx.x;
+  const TE* x = logits + (int64_t)n * ldV;
+  RowStat st{-INFINITY, 0.f, 0x7fffffff};
+  for (int v0 = tid * VEC; v0 < V; v0 += 256 * VEC) {
+    const uint4 q = *reinterpret_cast<const uint4*>(x + v0);
+    float f[VEC];
+    unpack<TE>(q, f);
+    float vm = -INFINITY;
+    int vi = 0;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      if (v0 + i >= V) f[i] = -INFINITY;
+      if (f[i] > vm) { vm = f[i]; vi = i; }     // strict: first (lowest) index wins
+    }
+    if (vm > st.m) {
+      st.s *= __expf(st.m - vm);                  // exp(-inf) = 0 on the first vector
+      st.m = vm;
+      st.idx = v0 + vi;
+    }
+    float e = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) e += __expf(f[i] - st.m);
+    st.s += e;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    RowStat other;
+    other.m = __shfl_xor(st.m, o, 64);
+    other.s = __shfl_xor(st.s, o, 64);
+    other.idx = __shfl_xor(st.idx, o, 64);
+    st = combine(st, other);
+  }
+  __shared__ RowStat ws[4];
+  if ((tid & 63) == 0) ws[tid >> 6] = st;
+  __syncthreads();
+  if (tid == 0) {
+    RowStat r = combine(combine(ws[0], ws[1]), combine(ws[2], ws[3]));
+    const float l = r.m + logf(r.s);
+    const int y = targets[n];
+    const bool nonpad = (y != pad_id) && (y >= 0) && (y < V);
+    const float loss = nonpad ? l - ld_elem<TE>(x, y) : 0.f;
+    lse[n] = l;
+    tok_loss_ws[n] = loss;
+    if (tok_loss) tok_loss[n] = loss;
+    if (argmax) argmax[n] = r.idx;
+    if (tgt_mask) tgt_mask[n] = nonpad ? 1 : 0;
+  }
+}
+
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ tok_loss_ws,
+                                                          const int32_t* __restrict__ targets, int N, int V,
+                                                          int pad_id, float* loss_sum, int32_t* n_tok) {
+  __shared__ double sd[1024];
+  __shared__ int sc[1024];
+  const int tid = threadIdx.x;
+  double acc = 0.0;
+  int cnt = 0;
+  for (int i = tid; i < N; i += 1024) {
+    acc += (double)tok_loss_ws[i];
+    const int y = targets[i];
+    cnt += ((y != pad_id) && (y >= 0) && (y < V)) ? 1 : 0;
+  }
+  sd[tid] = acc;
+  sc[tid] = cnt;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (tid < o) { sd[tid] += sd[tid + o]; sc[tid] += sc[tid + o]; }
+    __syncthreads();
+  }
+  if (tid == 0) { *loss_sum = (float)sd[0]; *n_tok = sc[0]; }
+}
+
+template <typename TE>
+__global__ __launch_bounds__(256) void xent_dlogits_kernel(TE* __restrict__ logits, int64_t ldV, int N, int V,
+                                                          const int32_t* __restrict__ targets, int pad_id,
+                                                          const float* __restrict__ lse, float g, int RB,
+                                                          float* __restrict__ db_partial) {
+  constexpr int VEC = Vec<TE>::N;
+  const int c0 = (blockIdx.x * 256 + threadIdx.x) * VEC;
+  if (c0 >= ldV) return;
+  const int r0 = blockIdx.y * RB;
+  const int r1 = r0 + RB < N ? r0 + RB : N;
+  float cs[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) cs[i] = 0.f;
+  for (int r = r0; r < r1; r += 4) {
+    uint4 q[4];
+    bool live[4];
+    int y[4];
+    float l[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int rr = r + u;
+      live[u] = false;
+      y[u] = -1;
+      l[u] = 0.f;
+      q[u] = make_uint4(0, 0, 0, 0);
+      if (rr < r1) {
+        y[u] = targets[rr];
+        live[u] = (y[u] != pad_id) && (y[u] >= 0) && (y[u] < V);
+        if (live[u]) {                      // pad rows are not read, only zeroed
+          l[u] = lse[rr];
+          q[u] = *reinterpret_cast<const uint4*>(logits + (int64_t)rr * ldV + c0);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int rr = r + u;
+      if (rr >= r1) break;
+      float f[VEC], d[VEC];
+      unpack<TE>(q[u], f);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        float v = 0.f;
+        if (live[u] && c0 + i < V) v = g * (__expf(f[i] - l[u]) - (c0 + i == y[u] ? 1.f : 0.f));
+        d[i] = v;
+        cs[i] += v;
+      }
+      *reinterpret_cast<uint4*>(logits + (int64_t)rr * ldV + c0) = pack<TE>(d);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VEC; ++i)
+    if (c0 + i < V) db_partial[(int64_t)blockIdx.y * V + c0 + i] = cs[i];
+}
+
+__global__ __launch_bounds__(256) void db_reduce_kernel(const float* __restrict__ db_partial, int nrb, int V,
+                                                       float* __restrict__ db_out) {
+  const int v = blockIdx.x * 256 + threadIdx.x;
+  if (v >= V) return;
+  float s = 0.f;
+  for (int r = 0; r < nrb; ++r) s += db_partial[(int64_t)r * V + v];
+  db_out[v] = s;
+}
+
+// ---- launchers ----------------------------------------------------------------
+hipError_t launch_xent_stats(const void* logits, int64_t ldV, bool e_bf16, int N, int V,
+                             const int32_t* targets, int pad_id, float* lse, float* tok_loss_ws,
+                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, hipStream_t st) {
+  if (e_bf16)
+    hipLaunchKernelGGL(xent_stats_kernel<uint16_t>, dim3(N), dim3(256), 0, st,
+                       reinterpret_cast<const uint16_t*>(logits), ldV, V, targets, pad_id, lse, tok_loss_ws,
+                       tok_loss, argmax, tgt_mask);
+  else
+    hipLaunchKernelGGL(xent_stats_kernel<float>, dim3(N), dim3(256), 0, st,
+                       reinterpret_cast<const float*>(logits), ldV, V, targets, pad_id, lse, tok_loss_ws, tok_loss,
+                       argmax, tgt_mask);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_reduce(const float* tok_loss_ws, const int32_t* targets, int N, int V, int pad_id,
+                              float* loss_sum, int32_t* n_tok, hipStream_t st) {
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, st, tok_loss_ws, targets, N, V, pad_id, loss_sum,
+                     n_tok);
+  return hipGetLastError();
+}
+
+int xent_rows_per_block(int N, int V, bool e_bf16) {
+  const int vec = e_bf16 ? 8 : 4;
+  const int64_t ldV = ((int64_t)V + 7) / 8 * 8;
+  const int64_t strips = (ldV + 256 * vec - 1) / (256 * vec);
+  int64_t rb = ((int64_t)N * strips + 4095) / 4096;
+  if (rb < 8) rb = 8;
+  if (rb > 256) rb = 256;
+  return (int)((rb + 3) / 4 * 4);
+}
+
+hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, int V, const int32_t* targets,
+                               int pad_id, const float* lse, float g, float* db_partial, hipStream_t st) {
+  const int vec = e_bf16 ? 8 : 4;
+  const int RB = xent_rows_per_block(N, V, e_bf16);
+  dim3 grid((unsigned)((ldV + 256 * vec - 1) / (256 * vec)), (N + RB - 1) / RB);
+  if (e_bf16)
+    hipLaunchKernelGGL(xent_dlogits_kernel<uint16_t>, grid, dim3(256), 0, st, reinterpret_cast<uint16_t*>(logits),
+                       ldV, N, V, targets, pad_id, lse, g, RB, db_partial);
+  else
+    hipLaunchKernelGGL(xent_dlogits_kernel<float>, grid, dim3(256), 0, st, reinterpret_cast<float*>(logits), ldV, N,
+                       V, targets, pad_id, lse, g, RB, db_partial);
+  return hipGetLastError();
+}
+
+hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st) {
+  hipLaunchKernelGGL(db_reduce_kernel, dim3((V + 255) / 256), dim3(256), 0, st, db_partial, nrb, V, db_out);
+  return hipGetLastError();
+}
+
+}  // namespace asx

@@ -95,6 +95,18 @@ class Inputs:
                       targets=np.ascontiguousarray(self.targets[:, b0:b1]),
                       grad_scale=self.grad_scale)
 
+    def take_sentences(self, idx) -> "Inputs":
+        """The listed sentences as a batch of their own (weights shared)."""
+        idx = np.asarray(idx, dtype=np.int64)
+        return Inputs(name=f"{self.name}[{len(idx)} sentences]", dtype=self.dtype, T=self.T, S=self.S,
+                      B=len(idx), H=self.H, V=self.V, pad_id=self.pad_id,
+                      h_dec=np.ascontiguousarray(self.h_dec[:, idx]),
+                      h_enc=np.ascontiguousarray(self.h_enc[:, idx]),
+                      src_len=np.ascontiguousarray(self.src_len[idx]),
+                      W_a=self.W_a, W_c=self.W_c, W_out=self.W_out, b_out=self.b_out,
+                      targets=np.ascontiguousarray(self.targets[:, idx]),
+                      grad_scale=self.grad_scale)
+
     def n_nonpad(self) -> int:
         t = self.targets
         return int(np.count_nonzero((t != self.pad_id) & (t >= 0) & (t < self.V)))

@@ -1,0 +1,114 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_1909_00562_amd as lib
+from paper_1909_00562_amd import binding as bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "attn_softmax.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_softmax_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    handle = lib.load_library()
+    names = _header_functions()
+    assert set(names) == set(bd.EXPORTS)
+    for n in names:
+        assert getattr(handle, n) is not None
+
+
+def _shape(**kw):
+    d = dict(T=8, S=8, B=4, H=64, V=1000, pad_id=0, dtype=bd.AS_F32, grad_scale=1.0)
+    d.update(kw)
+    return bd.AsShape(d["T"], d["S"], d["B"], d["H"], d["V"], d["pad_id"], d["dtype"], d["grad_scale"])
+
+
+def test_workspace_bytes():
+    assert bd.attn_softmax_workspace_bytes(_shape()) > 0
+    assert bd.attn_softmax_workspace_bytes(_shape(T=0)) == 0
+    assert bd.attn_softmax_workspace_bytes(_shape(pad_id=1000)) == 0
+    assert bd.attn_softmax_workspace_bytes(_shape(dtype=7)) == 0
+    assert bd.attn_softmax_workspace_bytes(_shape(dtype=bd.AS_BF16, H=60)) == 0
+    small = bd.attn_softmax_workspace_bytes(_shape(dtype=bd.AS_BF16))
+    big = bd.attn_softmax_workspace_bytes(_shape(dtype=bd.AS_BF16, V=2000))
+    assert big > small
+    # the stress configuration: logits dominate (N * V * 2 bytes = 4.19 GB)
+    s = _shape(T=64, S=64, B=256, H=2048, V=128000, dtype=bd.AS_BF16)
+    assert 4.19e9 < bd.attn_softmax_workspace_bytes(s) < 6e9
+
+
+def _call_fwd(shape, ptrs=None, ws_bytes=1 << 40, **over):
+    # fake, 16-byte aligned, never dereferenced addresses: every check below fails before a launch
+    a = dict(h_dec=0x1000, h_enc=0x2000, src_len=0x3000, W_a=0x4000, W_c=0x5000, W_out=0x6000, b_out=0x7000,
+             targets=0x8000, loss_sum=0x9000, n_tok=0xA000, tok_loss=None, argmax=None, attn_mask=None,
+             tgt_mask=None, workspace=0xB000)
+    a.update(over)
+    return bd.attn_softmax_fwd(shape, a["h_dec"], a["h_enc"], a["src_len"], a["W_a"], a["W_c"], a["W_out"],
+                               a["b_out"], a["targets"], a["loss_sum"], a["n_tok"], a["tok_loss"], a["argmax"],
+                               a["attn_mask"], a["tgt_mask"], a["workspace"], ws_bytes, 0, check=False)
+
+
+def _call_bwd(shape, ws_bytes=1 << 40, **over):
+    a = dict(h_dec=0x1000, h_enc=0x2000, src_len=0x3000, W_a=0x4000, W_c=0x5000, W_out=0x6000, b_out=0x7000,
+             targets=0x8000, workspace=0xB000, d_h_dec=0xC000, d_h_enc=0xD000, dW_a=0xE000, dW_c=0xF000,
+             dW_out=0x10000, db_out=0x11000)
+    a.update(over)
+    return bd.attn_softmax_bwd(shape, a["h_dec"], a["h_enc"], a["src_len"], a["W_a"], a["W_c"], a["W_out"],
+                               a["b_out"], a["targets"], a["workspace"], ws_bytes, a["d_h_dec"], a["d_h_enc"],
+                               a["dW_a"], a["dW_c"], a["dW_out"], a["db_out"], 0, check=False)
+
+
+def test_fwd_rejects_bad_arguments_before_launch():
+    assert _call_fwd(None) == 1                                   # AS_ERR_NULL
+    assert _call_fwd(_shape(), h_enc=None) == 1
+    assert _call_fwd(_shape(), loss_sum=None) == 1
+    assert "NULL" in bd.attn_softmax_last_error()
+    assert _call_fwd(_shape(S=0)) == 2                            # AS_ERR_SHAPE
+    assert _call_fwd(_shape(pad_id=-1)) == 2
+    assert _call_fwd(_shape(dtype=5)) == 3                        # AS_ERR_DTYPE
+    assert _call_fwd(_shape(), ws_bytes=128) == 4                 # AS_ERR_WORKSPACE
+    assert "needed" in bd.attn_softmax_last_error()
+    assert _call_fwd(_shape(), W_out=0x6004) == 5                 # AS_ERR_ALIGN
+    assert _call_fwd(_shape(dtype=bd.AS_BF16, H=60)) == 5
+
+
+def test_bwd_rejects_bad_arguments_before_launch():
+    assert _call_bwd(None) == 1
+    assert _call_bwd(_shape(), dW_out=None) == 1
+    assert _call_bwd(_shape(V=0)) == 2
+    assert _call_bwd(_shape(dtype=-1)) == 3
+    assert _call_bwd(_shape(), ws_bytes=0) == 4
+    assert _call_bwd(_shape(), db_out=0x11008) == 5
+
+
+def test_view_offsets_are_inside_the_workspace():
+    s = _shape(dtype=bd.AS_BF16, V=1003)
+    n = bd.attn_softmax_workspace_bytes(s)
+    base = 0x100000
+    seen = []
+    for which in range(5):
+        addr, nbytes, ld = bd.attn_softmax_view(s, base, which)
+        assert base <= addr and addr + nbytes <= base + n and addr % 16 == 0
+        seen.append((addr, addr + nbytes))
+        if which == bd.AS_VIEW_LOGITS:
+            assert ld == 1008                                     # rows padded to a multiple of 8
+    seen.sort()
+    for (a0, a1), (b0, b1) in zip(seen, seen[1:]):
+        assert a1 <= b0                                           # views do not overlap
+    with pytest.raises(bd.AttnSoftmaxError):
+        bd.attn_softmax_view(s, base, 99)
+
+
+def test_profile_calls_work_without_a_device():
+    bd.attn_softmax_profile_enable(False)
+    r = bd.attn_softmax_profile_read()
+    assert set(r) == set(bd.STAGE_NAMES) and all(v["launches"] == 0 for v in r.values())
