@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention-softmax path on one MI355X.
+
+One step = one forward + one backward pass of the whole path (every kernel of
+attn_softmax_fwd and attn_softmax_bwd) over one batch of synthetic input that
+is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress|large|mid|small|tiny]
+                    [--dtype bf16|f32] [--no-cpu-baseline]
+
+value      = non-pad target tokens per second, fwd+bwd, whole job (one GPU)
+roofline   = the kernel that takes the most time (a vocabulary GEMM): algorithmic
+             flops 2*N*H*V per launch / its average launch duration, measured with
+             HIP events on the launch stream inside the timed region, against the
+             dense bf16 MFMA peak (2.5 PFLOP/s)
+roofline_hbm = the two streaming softmax-cross-entropy kernels against the 8 TB/s
+             HBM peak (algorithmic bytes N*V*e for the statistics pass, 2*N*V*e for
+             the in-place dlogits pass)
+cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
+             sentences of the same workload (a reported baseline, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+GEMM_STAGES = {  # stage -> algorithmic flops per launch as a function of the shape
+    "gemm_logits": lambda N, H, V, T, S, B: 2.0 * N * H * V,
+    "gemm_dwout": lambda N, H, V, T, S, B: 2.0 * N * H * V,
+    "gemm_dhc": lambda N, H, V, T, S, B: 2.0 * N * H * V,
+    "gemm_q": lambda N, H, V, T, S, B: 2.0 * N * H * H,
+    "gemm_hc": lambda N, H, V, T, S, B: 4.0 * N * H * H,
+    "gemm_dwc": lambda N, H, V, T, S, B: 2.0 * N * H * H,      # per launch (two launches per step)
+    "gemm_dch": lambda N, H, V, T, S, B: 2.0 * N * H * H,      # per launch (two launches per step)
+    "gemm_dwa": lambda N, H, V, T, S, B: 2.0 * N * H * H,
+    "gemm_dh": lambda N, H, V, T, S, B: 2.0 * N * H * H,
+}
+
+
+def _traffic_from_profiles(workload: str, stage: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, if present."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(workload, {}).get(stage)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(inp, budget_s: float = 20.0):
+    """Oracle fwd+bwd on the first sentences of the batch, about `budget_s` seconds."""
+    from oracle import attn_softmax_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:  # pragma: no cover
+        cores = os.cpu_count() or 1
+    args = (inp.h_dec, inp.h_enc, inp.src_len, inp.W_a, inp.W_c, inp.W_out, inp.b_out, inp.targets, inp.pad_id)
+
+    def run(sent):
+        t0 = time.perf_counter()
+        orc.forward(*args, keep_logits=False, sentences=sent)
+        orc.backward(*args, grad_scale=inp.grad_scale, sentences=sent)
+        return time.perf_counter() - t0
+
+    t1 = run([0])                      # one sentence: sizes the sample (and warms the BLAS threads)
+    n = int(max(1, min(inp.B, budget_s / max(t1, 1e-6))))
+    sent = list(range(n))
+    dt = run(sent)
+    tgt = inp.targets[:, :n]
+    tokens = int(((tgt != inp.pad_id) & (tgt >= 0) & (tgt < inp.V)).sum())
+    return {"value": tokens / dt, "unit": "target tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"float64 numpy oracle fwd+bwd on sentences 0..{n - 1} of the {inp.name} batch "
+                      f"({tokens} non-pad tokens, {inp.T * n} positions) in {dt:.2f} s",
+            "positions_per_s": inp.T * n / dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="stress", choices=["tiny", "small", "mid", "large", "stress"])
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f32"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stage-events", action="store_true",
+                    help="do not bracket kernels with HIP events inside the timed region")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs the path on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_1909_00562_amd as lib
+    from synth_inputs import make_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    lib.load_library()                                   # fails loudly if the HIP library is not built
+
+    inp = make_inputs(a.workload, dtype=a.dtype)
+    db = lib.DeviceBatch(inp)
+    T, S, B, H, V = inp.T, inp.S, inp.B, inp.H, inp.V
+    N = T * B
+    e = 2 if inp.dtype == "bf16" else 4
+    n_tok = inp.n_nonpad()
+
+    def step():
+        db.fwd()
+        db.bwd()
+
+    for _ in range(a.warmup):
+        step()
+    db.sync()
+    lib.attn_softmax_profile_enable(not a.no_stage_events)
+    db.sync()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    db.sync()
+    dt = time.perf_counter() - t0
+    stages = lib.attn_softmax_profile_read()
+    lib.attn_softmax_profile_enable(False)
+    assert int(db.n_tok.item()) == n_tok
+
+    ms_step = dt / a.steps * 1e3
+    per_stage = {k: (v["ms"] / v["launches"] if v["launches"] else 0.0) for k, v in stages.items()}
+    step_ms_by_stage = {k: v["ms"] / a.steps for k, v in stages.items() if v["launches"]}
+
+    roofline = None
+    roofline_hbm = None
+    if not a.no_stage_events:
+        gemm_ms = {k: step_ms_by_stage.get(k, 0.0) for k in GEMM_STAGES}
+        dom = max(gemm_ms, key=gemm_ms.get)
+        flops = GEMM_STAGES[dom](N, H, V, T, S, B)
+        avg_ms = per_stage[dom]
+        ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+        bf = inp.dtype == "bf16"
+        peak = PEAK_MFMA_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
+        roofline = {"kernel": dom, "bound": "mfma" if bf else "alu", "achieved": ach, "peak": peak,
+                    "unit": "TFLOP/s", "frac": ach / peak, "avg_launch_ms": avg_ms,
+                    "flops_per_launch": flops, "traffic": _traffic_from_profiles(a.workload, dom)}
+        # all three vocabulary GEMMs together (they are >90 % of the path's flops)
+        voc_ms = sum(step_ms_by_stage.get(k, 0.0) for k in ("gemm_logits", "gemm_dwout", "gemm_dhc"))
+        if voc_ms > 0:
+            roofline["vocab_gemms_tflops"] = 6.0 * N * H * V / (voc_ms * 1e-3) / 1e12
+        sb = float(N) * V * e
+        st_ms, dl_ms = per_stage.get("xent_stats", 0.0), per_stage.get("xent_dlogits", 0.0)
+        tot = st_ms + dl_ms
+        if tot > 0:
+            ach_b = 3.0 * sb / (tot * 1e-3) / 1e9
+            roofline_hbm = {"kernel": "xent_stats+xent_dlogits", "bound": "hbm", "achieved": ach_b,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach_b / PEAK_HBM_GBS,
+                            "bytes_per_step": 3.0 * sb,
+                            "xent_stats": {"avg_launch_ms": st_ms, "GB/s": sb / (st_ms * 1e-3) / 1e9 if st_ms else 0},
+                            "xent_dlogits": {"avg_launch_ms": dl_ms,
+                                             "GB/s": 2 * sb / (dl_ms * 1e-3) / 1e9 if dl_ms else 0},
+                            "traffic": _traffic_from_profiles(a.workload, "xent")}
+
+    out = {
+        "metric": "attn_softmax_fwd_bwd_target_tokens_per_sec",
+        "value": n_tok / (dt / a.steps),
+        "unit": "target tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": inp.dtype, "data": "synthetic",
+        "config": {"workload": a.workload, "B": B, "T": T, "S": S, "H": H, "V": V, "positions": N,
+                   "non_pad_tokens": n_tok, "grad_scale": inp.grad_scale},
+        "positions_per_sec": N / (dt / a.steps),
+        "path_tflops": (6.0 * N * H * V + 18.0 * N * H * H + 12.0 * B * T * S * H) / (dt / a.steps) / 1e12,
+        "roofline": roofline,
+        "roofline_hbm": roofline_hbm,
+        "stage_ms_per_step": {k: round(v, 5) for k, v in step_ms_by_stage.items()},
+    }
+    if not a.no_cpu_baseline:
+        del db
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
