@@ -3,16 +3,25 @@
 // One kernel template covers the three operand orientations the path needs
 // (both operands reduction-contiguous; B stored [K,N]; A and B stored [K,*]).
 // Whatever the orientation in memory, a block tile lands in LDS as rows of 64
-// reduction elements (128 bytes), 16-byte chunks XOR-swizzled by the row index
-// so that both the tile stores and the 16-byte MFMA fragment reads are free of
-// bank conflicts.  Operands whose reduction index is the strided one are
-// transposed in registers (4 k-rows x 8 columns per lane, v_perm_b32) on their
-// way from the global loads to LDS.  The main loop is double buffered in LDS
-// with the next tile's global loads in flight during the MFMAs.
+// reduction elements (128 bytes) whose 16-byte chunks are XOR-swizzled by the
+// row index, so tile writes and the 16-byte MFMA fragment reads are free of bank
+// conflicts.
+//   * Reduction-contiguous operands go HBM -> LDS directly
+//     (buffer_load_dwordx4 ... lds): no staging registers, no ds_write.  The
+//     swizzle is applied on the global side: lane l of a wave-wide load fills
+//     LDS slot l of an 8-row group and fetches the chunk that belongs there.
+//   * Operands whose reduction index is the strided one are loaded 16 bytes
+//     along their contiguous index, transposed in registers (4 k-rows x 8
+//     columns per lane, v_perm_b32) and written with ds_write_b64.
+// Out-of-range rows / reduction indices are redirected to an offset beyond the
+// buffer resource's range, for which the hardware returns zeros: no branches.
+// The main loop is double buffered in LDS: the loads of tile k+1 are in flight
+// while the MFMAs of tile k run; one barrier per tile.
 //
-// Wave tiling: 256 threads = 2 x 2 waves, each wave owns (BM/2) x (BN/2) of the
-// block tile as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16, 8 reduction
-// elements per lane per operand).
+// Tiling: 256x256x64 block tile with 8 waves (2 x 4, two per SIMD, wave tile
+// 128x64) or 128x128x64 with 4 waves (wave tile 64x64); MFMA 32x32x16 bf16.
+// The epilogue stages each wave's accumulators through its own slice of LDS so
+// that global stores are 8/16-byte vectors along rows.
 #include "common.h"
 #include "gemm.h"
 
@@ -35,71 +44,75 @@ struct GemmDev {
   int splits;
   float* partial;
   int tiles_m, tiles_n;
-  int kper;  // reduction elements per split, multiple of 64
+  int kper;    // reduction elements per split, multiple of 64
+  int vec_ok;  // rows of C (and C_lo, C_dact, gate) allow 8/16-byte vector access
 };
 
-constexpr int BK = 64;          // reduction elements per LDS tile row
-constexpr int ROWB = BK * 2;    // bytes per LDS tile row
+constexpr int BK = 64;                  // reduction elements per LDS tile row
+constexpr int ROWB = BK * 2;            // bytes per LDS tile row
+constexpr uint32_t kOob = 0x80000000u;  // offset outside every buffer resource below
 
-// ---- global -> registers ---------------------------------------------------
-template <int ROWS, bool KC>
-__device__ __forceinline__ void tile_gload(uint4 (&r)[ROWS / 32], const uint16_t* __restrict__ X,
-                                           int64_t ld, int row0, int R, int k0, int kend, int tid) {
-  const uint4 zero = make_uint4(0, 0, 0, 0);
-  if constexpr (KC) {
-    const int c = tid & 7, rr = tid >> 3;
-    const int gk = k0 + c * 8;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+  // raw buffer, 2 GiB range: offsets >= 2^31 (kOob) read as zero
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+
+// ---- reduction-contiguous operand: HBM -> LDS, no registers ----------------------
+// The tile's ROWS rows are split into groups of 8 rows (1 KiB of LDS); one wave-wide
+// 16-byte load fills one group.  X points at element (row0, k0) of the operand.
+template <int ROWS, int NW>
+__device__ __forceinline__ void tile_load_direct(const uint16_t* X, int64_t ld, int rows_left, int k_left,
+                                                 unsigned char* lds_tile, int wave, int lane) {
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(X);
+  const int rl = lane >> 3;           // row inside the group
+  const int chunk = (lane & 7) ^ rl;  // logical 16-byte chunk that belongs in LDS slot `lane`
+  const bool kok = chunk * 8 < k_left;
 #pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {
-      const int gr = row0 + rr + 32 * j;
-      const bool ok = (gr < R) && (gk < kend);
-      r[j] = ok ? *reinterpret_cast<const uint4*>(X + (int64_t)gr * ld + gk) : zero;
-    }
-  } else {
-    const int lane = tid & 63, w = tid >> 6;
-    const int kq = lane & 15, rb = w * 4 + (lane >> 4);
+  for (int j = 0; j < ROWS / 8 / NW; ++j) {
+    const int g = wave + NW * j;
+    const int r = g * 8 + rl;
+    const uint32_t off = (kok && r < rows_left) ? (uint32_t)(((int64_t)r * ld + chunk * 8) * 2) : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + g * 1024), 16, off, 0, 0, 0);
+  }
+}
+
+// ---- strided-reduction operand: HBM -> registers (transposed later) ----------------
+// Thread t owns rows (t/16)*8 .. +7 (contiguous index) x reduction rows (t%16)*4 .. +3.
+// X points at element (k0, row0) of the operand stored [K, rows].
+template <int ROWS, int NT>
+__device__ __forceinline__ void tile_load_regs(u32x4_t (&r)[ROWS * 2 / NT * 4], const uint16_t* X, int64_t ld,
+                                               int rows_left, int k_left, int tid) {
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(X);
+  const int kq = tid & 15, rb = tid >> 4;
 #pragma unroll
-    for (int j = 0; j < ROWS / 128; ++j) {
-      const int gr = row0 + (rb + 16 * j) * 8;
+  for (int j = 0; j < ROWS * 2 / NT; ++j) {
+    const int row = (rb + (NT / 16) * j) * 8;
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int gk = k0 + kq * 4 + kk;
-        const bool ok = (gk < kend) && (gr < R);
-        r[j * 4 + kk] = ok ? *reinterpret_cast<const uint4*>(X + (int64_t)gk * ld + gr) : zero;
-      }
+    for (int kk = 0; kk < 4; ++kk) {
+      const int k = kq * 4 + kk;
+      const uint32_t off = (k < k_left && row < rows_left) ? (uint32_t)(((int64_t)k * ld + row) * 2) : kOob;
+      r[j * 4 + kk] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
     }
   }
 }
 
-__device__ __forceinline__ uint32_t u4_get(const uint4& v, int i) {
-  return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
-}
-
-// ---- registers -> LDS (swizzled, reduction-contiguous rows) -----------------
-template <int ROWS, bool KC>
-__device__ __forceinline__ void tile_sstore(const uint4 (&r)[ROWS / 32], unsigned char* base, int tid) {
-  if constexpr (KC) {
-    const int c = tid & 7, rr = tid >> 3;
+template <int ROWS, int NT>
+__device__ __forceinline__ void tile_store_transposed(const u32x4_t (&r)[ROWS * 2 / NT * 4], unsigned char* lds_tile,
+                                                      int tid) {
+  const int kq = tid & 15, rb = tid >> 4;
+  const int chunk = kq >> 1, half = kq & 1;
 #pragma unroll
-    for (int j = 0; j < ROWS / 32; ++j) {
-      const int row = rr + 32 * j;
-      *reinterpret_cast<uint4*>(base + row * ROWB + ((c ^ (row & 7)) << 4)) = r[j];
-    }
-  } else {
-    const int lane = tid & 63, w = tid >> 6;
-    const int kq = lane & 15, rb = w * 4 + (lane >> 4);
-    const int chunk = kq >> 1, half = kq & 1;
+  for (int j = 0; j < ROWS * 2 / NT; ++j) {
 #pragma unroll
-    for (int j = 0; j < ROWS / 128; ++j) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int row = (rb + 16 * j) * 8 + e;
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        const int dw = e >> 1;
-        const uint32_t lo = __builtin_amdgcn_perm(u4_get(r[j * 4 + 1], dw), u4_get(r[j * 4 + 0], dw), sel);
-        const uint32_t hi = __builtin_amdgcn_perm(u4_get(r[j * 4 + 3], dw), u4_get(r[j * 4 + 2], dw), sel);
-        *reinterpret_cast<uint2*>(base + row * ROWB + ((chunk ^ e) << 4) + half * 8) = make_uint2(lo, hi);
-      }
+    for (int e = 0; e < 8; ++e) {
+      const int row = (rb + (NT / 16) * j) * 8 + e;
+      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+      const uint32_t lo = __builtin_amdgcn_perm(r[j * 4 + 1][e >> 1], r[j * 4 + 0][e >> 1], sel);
+      const uint32_t hi = __builtin_amdgcn_perm(r[j * 4 + 3][e >> 1], r[j * 4 + 2][e >> 1], sel);
+      *reinterpret_cast<uint2*>(lds_tile + row * ROWB + ((chunk ^ e) << 4) + half * 8) = make_uint2(lo, hi);
     }
   }
 }
@@ -108,15 +121,19 @@ __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row
   return *reinterpret_cast<const bf16x8_t*>(base + row * ROWB + ((chunk ^ (row & 7)) << 4));
 }
 
-template <int BM, int BN, bool AKC, bool BKC, bool OUT_BF16>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev p) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-  constexpr int NA = BM / 32, NB = BN / 32;
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
+  constexpr int NW = WGM * WGN, NT = 64 * NW;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * ROWB;
-  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int RA = AKC ? 1 : BM * 2 / NT * 4, RB = BKC ? 1 : BN * 2 / NT * 4;
+  static_assert(WN == 64 && (WM == 64 || WM == 128), "epilogue assumes 64-column wave tiles");
+  static_assert(2 * STAGE >= NW * 16384, "epilogue needs 16 KiB of LDS per wave");
+  extern __shared__ __align__(1024) unsigned char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: LDS bases of direct loads
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // --- block -> tile: consecutive blocks go round-robin to the 8 XCDs, so give
   // each XCD a contiguous run of tiles, then walk tiles in groups of 8 tile
@@ -163,9 +180,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[NA], rb[NB];
+  u32x4_t ra[RA], rb[RB];
 
-  auto issue = [&](int kt) {
+  // start the loads of reduction tile kt (straight into LDS stage `stage` where possible)
+  auto issue = [&](int kt, int stage) {
     int seg = 0;
 #pragma unroll
     for (int s = 0; s < kMaxSeg - 1; ++s)
@@ -174,27 +192,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev p) {
         seg = s + 1;
       }
     const int k0 = (seg == 0 ? kbeg0 : 0) + kt * BK;
-    const int kend = seg == 0 ? kend0 : p.K[seg];
+    const int k_left = (seg == 0 ? kend0 : p.K[seg]) - k0;
     const uint16_t* A = p.A[seg] + (int64_t)batch * p.sA[seg];
     const uint16_t* B = p.B[seg] + (int64_t)batch * p.sB[seg];
-    tile_gload<BM, AKC>(ra, A, p.lda[seg], m0, p.M, k0, kend, tid);
-    tile_gload<BN, BKC>(rb, B, p.ldb[seg], n0, p.N, k0, kend, tid);
+    const int64_t lda = p.lda[seg], ldb = p.ldb[seg];
+    unsigned char* as = smem + stage * STAGE;
+    unsigned char* bs = as + BM * ROWB;
+    if constexpr (AKC)
+      tile_load_direct<BM, NW>(A + (int64_t)m0 * lda + k0, lda, p.M - m0, k_left, as, wave, lane);
+    else
+      tile_load_regs<BM, NT>(ra, A + (int64_t)k0 * lda + m0, lda, p.M - m0, k_left, tid);
+    if constexpr (BKC)
+      tile_load_direct<BN, NW>(B + (int64_t)n0 * ldb + k0, ldb, p.N - n0, k_left, bs, wave, lane);
+    else
+      tile_load_regs<BN, NT>(rb, B + (int64_t)k0 * ldb + n0, ldb, p.N - n0, k_left, tid);
   };
+  // finish them: transposed operands go registers -> LDS here
   auto commit = [&](int stage) {
     unsigned char* as = smem + stage * STAGE;
-    tile_sstore<BM, AKC>(ra, as, tid);
-    tile_sstore<BN, BKC>(rb, as + BM * ROWB, tid);
+    unsigned char* bs = as + BM * ROWB;
+    if constexpr (!AKC) tile_store_transposed<BM, NT>(ra, as, tid);
+    if constexpr (!BKC) tile_store_transposed<BN, NT>(rb, bs, tid);
   };
 
   if (nk > 0) {
-    issue(0);
+    issue(0, 0);
     commit(0);
   }
+  __builtin_amdgcn_s_waitcnt(0);  // this wave's direct loads have landed in LDS
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
     const bool more = kt + 1 < nk;
-    if (more) issue(kt + 1);
+    if (more) issue(kt + 1, (kt + 1) & 1);
     const unsigned char* as = smem + (kt & 1) * STAGE;
     const unsigned char* bs = as + BM * ROWB;
 #pragma unroll
@@ -212,60 +242,123 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmDev p) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
     if (more) commit((kt + 1) & 1);
+    __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   }
 
-  // --- epilogue.  MFMA 32x32 output: register r of lane l holds
-  // row 8*(r/4) + 4*(l/32) + r%4, column l%32 of the tile.
+  // --- epilogue.  MFMA 32x32 output: register r of lane l holds row
+  // 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.  Each wave stages 64 rows x
+  // 64 columns at a time through its own 16 KiB of LDS and reads them back as
+  // 4-column vectors (16 lanes per row), so the global accesses are row-contiguous.
+  float* stage_f = reinterpret_cast<float*>(smem + wave * 16384);
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-  if (p.splits > 1) {
-    float* P = p.partial + (int64_t)z * p.M * p.N;
+  const int vcol = (lane & 15) * 4, vrow = lane >> 4;
+  const int gcol = n0 + wn * WN + vcol;
+  float* Pz = p.splits > 1 ? p.partial + (int64_t)z * p.M * p.N : nullptr;
+  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (p.bias && p.splits <= 1) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = n0 + wn * WN + j * 32 + col_l;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * WM + i * 32 + (r >> 2) * 8 + row_l + (r & 3);
-          if (row < p.M && col < p.N) P[(int64_t)row * p.N + col] = acc[i][j][r];
-        }
-      }
-    return;
+    for (int c = 0; c < 4; ++c)
+      if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
   }
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int half = 0; half < TM / 2; ++half) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * WN + j * 32 + col_l;
-      if (col >= p.N) continue;
-      const float bias = p.bias ? bf16_bits_to_f32(p.bias[col]) : 0.f;
+    for (int i2 = 0; i2 < 2; ++i2)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WM + i * 32 + (r >> 2) * 8 + row_l + (r & 3);
-        if (row >= p.M) continue;
-        float v = acc[i][j][r] + bias;
-        if (p.act_tanh) v = tanhf(v);
-        if (p.gate) v *= p.gate[(int64_t)row * p.ldg + col];
-        const int64_t ci = (int64_t)batch * p.sC + (int64_t)row * p.ldc + col;
-        if constexpr (OUT_BF16) {
-          const uint32_t hi = f32_to_bf16_bits(v);
-          reinterpret_cast<uint16_t*>(p.C)[ci] = (uint16_t)hi;
-          if (p.C_lo) p.C_lo[ci] = (uint16_t)f32_to_bf16_bits(v - bf16_bits_to_f32(hi));
-          if (p.C_dact) p.C_dact[ci] = 1.f - v * v;
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          stage_f[(i2 * 32 + (r >> 2) * 8 + row_l + (r & 3)) * 64 + j * 32 + col_l] = acc[half * 2 + i2][j][r];
+    __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+      const int lr = it * 4 + vrow;
+      const int grow = m0 + wm * WM + half * 64 + lr;
+      if (grow >= p.M || gcol >= p.N) continue;
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * 64 + vcol);
+      float v[4] = {v4[0], v4[1], v4[2], v4[3]};
+      if (Pz) {
+        float* dst = Pz + (int64_t)grow * p.N + gcol;
+        if (gcol + 3 < p.N && (p.N & 3) == 0) {
+          *reinterpret_cast<f32x4_t*>(dst) = v4;
         } else {
-          float* C = reinterpret_cast<float*>(p.C);
-          if (p.accumulate) v += C[ci];
-          C[ci] = v;
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) dst[c] = v[c];
+        }
+        continue;
+      }
+      const bool vec = p.vec_ok && gcol + 3 < p.N;
+      const int64_t ci = (int64_t)batch * p.sC + (int64_t)grow * p.ldc + gcol;
+      float gt[4] = {1.f, 1.f, 1.f, 1.f};
+      if (p.gate) {
+        const float* gp = p.gate + (int64_t)grow * p.ldg + gcol;
+        if (vec) {
+          const f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(gp);
+          gt[0] = g4[0]; gt[1] = g4[1]; gt[2] = g4[2]; gt[3] = g4[3];
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) gt[c] = gp[c];
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float x = v[c] + bias4[c];
+        if (p.act_tanh) x = tanhf(x);
+        v[c] = x * gt[c];
+      }
+      if constexpr (OUT_BF16) {
+        uint16_t* C = reinterpret_cast<uint16_t*>(p.C) + ci;
+        uint32_t hb[4];
+        float lo[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          hb[c] = f32_to_bf16_bits(v[c]);
+          lo[c] = v[c] - bf16_bits_to_f32(hb[c]);
+        }
+        if (vec) {
+          *reinterpret_cast<uint2*>(C) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
+          if (p.C_lo)
+            *reinterpret_cast<uint2*>(p.C_lo + ci) = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
+          if (p.C_dact) {
+            f32x4_t d4 = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
+            *reinterpret_cast<f32x4_t*>(p.C_dact + ci) = d4;
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) {
+              C[c] = (uint16_t)hb[c];
+              if (p.C_lo) p.C_lo[ci + c] = (uint16_t)f32_to_bf16_bits(lo[c]);
+              if (p.C_dact) p.C_dact[ci + c] = 1.f - v[c] * v[c];
+            }
+        }
+      } else {
+        float* C = reinterpret_cast<float*>(p.C) + ci;
+        if (vec) {
+          if (p.accumulate) {
+            const f32x4_t o4 = *reinterpret_cast<const f32x4_t*>(C);
+            v[0] += o4[0]; v[1] += o4[1]; v[2] += o4[2]; v[3] += o4[3];
+          }
+          f32x4_t s4 = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4_t*>(C) = s4;
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) C[c] = p.accumulate ? v[c] + C[c] : v[c];
         }
       }
     }
+    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next half overwrites the slice
+  }
 }
 
-template <int BM, int BN, bool AKC, bool BKC, bool OUT_BF16>
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
 static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = 2 * (BM + BN) * ROWB;
-  auto kfn = gemm_bf16_kernel<BM, BN, AKC, BKC, OUT_BF16>;
+  auto kfn = gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC, OUT_BF16>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -274,24 +367,26 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
     attr_set = true;
   }
   dim3 grid(d.tiles_m * d.tiles_n, 1, batch * d.splits);
-  hipLaunchKernelGGL(kfn, grid, dim3(256), smem, st, d);
+  hipLaunchKernelGGL(kfn, grid, dim3(64 * WGM * WGN), smem, st, d);
   return hipGetLastError();
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int WGM, int WGN>
 static hipError_t launch_tile(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
   const bool obf = g.c_bf16 && g.splits <= 1;
   if (g.a_kc && g.b_kc)
-    return obf ? launch_one<BM, BN, true, true, true>(d, g.batch, st)
-               : launch_one<BM, BN, true, true, false>(d, g.batch, st);
+    return obf ? launch_one<BM, BN, WGM, WGN, true, true, true>(d, g.batch, st)
+               : launch_one<BM, BN, WGM, WGN, true, true, false>(d, g.batch, st);
   if (g.a_kc && !g.b_kc)
-    return obf ? launch_one<BM, BN, true, false, true>(d, g.batch, st)
-               : launch_one<BM, BN, true, false, false>(d, g.batch, st);
+    return obf ? launch_one<BM, BN, WGM, WGN, true, false, true>(d, g.batch, st)
+               : launch_one<BM, BN, WGM, WGN, true, false, false>(d, g.batch, st);
   if (!g.a_kc && !g.b_kc)
-    return obf ? launch_one<BM, BN, false, false, true>(d, g.batch, st)
-               : launch_one<BM, BN, false, false, false>(d, g.batch, st);
+    return obf ? launch_one<BM, BN, WGM, WGN, false, false, true>(d, g.batch, st)
+               : launch_one<BM, BN, WGM, WGN, false, false, false>(d, g.batch, st);
   return hipErrorInvalidValue;  // (A strided, B contiguous) is not used by the path
 }
+
+static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   if (g.M < 1 || g.N < 1 || g.batch < 1 || g.splits < 1) return hipErrorInvalidValue;
@@ -307,10 +402,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
     d.sB[s] = g.sB[s];
     d.K[s] = g.K[s];
     if (g.K[s] > 0) {
-      // 16-byte vector loads: leading dimensions and batch strides in units of 8 elements
+      // 16-byte vector loads: leading dimensions and batch strides in units of 8 elements;
+      // 32-bit byte offsets inside one 256-row (or 64-reduction-row) tile
       if ((g.lda[s] & 7) || (g.ldb[s] & 7) || (g.sA[s] & 7) || (g.sB[s] & 7)) return hipErrorInvalidValue;
-      if ((reinterpret_cast<uintptr_t>(g.A[s]) & 15) || (reinterpret_cast<uintptr_t>(g.B[s]) & 15))
-        return hipErrorInvalidValue;
+      if (g.lda[s] >= (1 << 22) || g.ldb[s] >= (1 << 22)) return hipErrorInvalidValue;
+      if (!al16(g.A[s]) || !al16(g.B[s])) return hipErrorInvalidValue;
     }
   }
   d.M = g.M;
@@ -327,13 +423,17 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   d.accumulate = g.accumulate;
   d.splits = g.splits;
   d.partial = g.partial;
+  // vector epilogue: every row of C / C_lo / C_dact / gate starts 16-byte aligned
+  // (ldc % 4 == 0 gives 8-byte alignment for bf16 rows, which their 8-byte stores need)
+  d.vec_ok = ((g.ldc & 3) == 0) && ((g.sC & 3) == 0) && al16(g.C) && (!g.C_lo || al16(g.C_lo)) &&
+             (!g.C_dact || al16(g.C_dact)) && (!g.gate || (al16(g.gate) && (g.ldg & 3) == 0));
   const int bm = big_tile ? 256 : 128;
   d.tiles_m = (g.M + bm - 1) / bm;
   d.tiles_n = (g.N + bm - 1) / bm;
   const int ktiles = (g.K[0] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
-  return big_tile ? launch_tile<256, 256>(g, d, st) : launch_tile<128, 128>(g, d, st);
+  return big_tile ? launch_tile<256, 256, 2, 4>(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
 }
 
 }  // namespace asx
