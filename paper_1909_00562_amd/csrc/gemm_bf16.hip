@@ -4,8 +4,9 @@
 // (both operands reduction-contiguous; B stored [K,N]; A and B stored [K,*]).
 // Whatever the orientation in memory, a block tile lands in LDS as rows of 64
 // reduction elements (128 bytes) whose 16-byte chunks are XOR-swizzled by the
-// row index, so tile writes and the 16-byte MFMA fragment reads are free of bank
-// conflicts.
+// row index (chunk ^ (row & 7) ^ ((row >> 3) & 1): 16 consecutive rows of one
+// chunk column land in 16 different 16-byte bank groups of the 64-bank LDS), so
+// tile writes and the 16-byte MFMA fragment reads are free of bank conflicts.
 //   * Reduction-contiguous operands go HBM -> LDS directly
 //     (buffer_load_dwordx4 ... lds): no staging registers, no ds_write.  The
 //     swizzle is applied on the global side: lane l of a wave-wide load fills
@@ -62,63 +63,77 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
 
 // ---- reduction-contiguous operand: HBM -> LDS, no registers ----------------------
 // The tile's ROWS rows are split into groups of 8 rows (1 KiB of LDS); one wave-wide
-// 16-byte load fills one group.  X points at element (row0, k0) of the operand.
+// 16-byte load fills one group.  Per-lane byte offsets relative to element
+// (row0, k0) are computed once per kernel; rows beyond the operand get kOob.
 template <int ROWS, int NW>
-__device__ __forceinline__ void tile_load_direct(const uint16_t* X, int64_t ld, int rows_left, int k_left,
-                                                 unsigned char* lds_tile, int wave, int lane) {
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(X);
-  const int rl = lane >> 3;           // row inside the group
-  const int chunk = (lane & 7) ^ rl;  // logical 16-byte chunk that belongs in LDS slot `lane`
-  const bool kok = chunk * 8 < k_left;
+struct DirectLoader {
+  static constexpr int NL = ROWS / 8 / NW;   // loads per wave and tile
+  uint32_t voff[NL];
+  int chunk8;                                // first reduction element of this lane's chunk
+  __device__ __forceinline__ void init(int64_t ld, int rows_left, int wave, int lane) {
+    static_assert(NW % 2 == 0, "swizzle below assumes the parity of the row group is the wave's");
+    const int rl = lane >> 3;                        // row inside the group
+    const int chunk = (lane & 7) ^ rl ^ (wave & 1);  // logical 16-byte chunk that belongs in LDS slot `lane`
+    chunk8 = chunk * 8;
 #pragma unroll
-  for (int j = 0; j < ROWS / 8 / NW; ++j) {
-    const int g = wave + NW * j;
-    const int r = g * 8 + rl;
-    const uint32_t off = (kok && r < rows_left) ? (uint32_t)(((int64_t)r * ld + chunk * 8) * 2) : kOob;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + g * 1024), 16, off, 0, 0, 0);
+    for (int j = 0; j < NL; ++j) {
+      const int r = (wave + NW * j) * 8 + rl;
+      voff[j] = r < rows_left ? (uint32_t)(((int64_t)r * ld + chunk * 8) * 2) : kOob;
+    }
   }
-}
+  // X points at element (row0, k0); k_left = reduction elements left from k0
+  __device__ __forceinline__ void load(int j, const __amdgpu_buffer_rsrc_t& rs, int k_left, unsigned char* lds_tile,
+                                       int wave) const {
+    const uint32_t off = chunk8 < k_left ? voff[j] : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + (wave + NW * j) * 1024), 16, off, 0, 0, 0);
+  }
+};
 
-// ---- strided-reduction operand: HBM -> registers (transposed later) ----------------
+// ---- strided-reduction operand: HBM -> registers -> transposed into LDS --------------
 // Thread t owns rows (t/16)*8 .. +7 (contiguous index) x reduction rows (t%16)*4 .. +3.
-// X points at element (k0, row0) of the operand stored [K, rows].
 template <int ROWS, int NT>
-__device__ __forceinline__ void tile_load_regs(u32x4_t (&r)[ROWS * 2 / NT * 4], const uint16_t* X, int64_t ld,
-                                               int rows_left, int k_left, int tid) {
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(X);
-  const int kq = tid & 15, rb = tid >> 4;
+struct TransposeLoader {
+  static constexpr int NB = ROWS * 2 / NT;   // 4x8 blocks per thread
+  static constexpr int NL = NB * 4;          // 16-byte loads per thread and tile
+  uint32_t voff[NL];
+  u32x4_t r[NL];
+  int k4;
+  __device__ __forceinline__ void init(int64_t ld, int rows_left, int tid) {
+    const int kq = tid & 15, rb = tid >> 4;
+    k4 = kq * 4;
 #pragma unroll
-  for (int j = 0; j < ROWS * 2 / NT; ++j) {
-    const int row = (rb + (NT / 16) * j) * 8;
+    for (int j = 0; j < NB; ++j) {
+      const int row = (rb + (NT / 16) * j) * 8;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const int k = kq * 4 + kk;
-      const uint32_t off = (k < k_left && row < rows_left) ? (uint32_t)(((int64_t)k * ld + row) * 2) : kOob;
-      r[j * 4 + kk] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+      for (int kk = 0; kk < 4; ++kk)
+        voff[j * 4 + kk] = row < rows_left ? (uint32_t)(((int64_t)(k4 + kk) * ld + row) * 2) : kOob;
     }
   }
-}
-
-template <int ROWS, int NT>
-__device__ __forceinline__ void tile_store_transposed(const u32x4_t (&r)[ROWS * 2 / NT * 4], unsigned char* lds_tile,
-                                                      int tid) {
-  const int kq = tid & 15, rb = tid >> 4;
-  const int chunk = kq >> 1, half = kq & 1;
+  // X points at element (k0, row0) of the operand stored [K, rows]
+  __device__ __forceinline__ void load(int l, const __amdgpu_buffer_rsrc_t& rs, int k_left) {
+    const uint32_t off = (k4 + (l & 3)) < k_left ? voff[l] : kOob;
+    r[l] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+  }
+  __device__ __forceinline__ void store(unsigned char* lds_tile, int tid) const {
+    static_assert((NT / 16) % 2 == 0, "row-group parity must not depend on j");
+    const int kq = tid & 15, rb = tid >> 4;
+    const int chunk = (kq >> 1) ^ (rb & 1), half = kq & 1;
 #pragma unroll
-  for (int j = 0; j < ROWS * 2 / NT; ++j) {
+    for (int j = 0; j < NB; ++j) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int row = (rb + (NT / 16) * j) * 8 + e;
-      const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-      const uint32_t lo = __builtin_amdgcn_perm(r[j * 4 + 1][e >> 1], r[j * 4 + 0][e >> 1], sel);
-      const uint32_t hi = __builtin_amdgcn_perm(r[j * 4 + 3][e >> 1], r[j * 4 + 2][e >> 1], sel);
-      *reinterpret_cast<uint2*>(lds_tile + row * ROWB + ((chunk ^ e) << 4) + half * 8) = make_uint2(lo, hi);
+      for (int e = 0; e < 8; ++e) {
+        const int row = (rb + (NT / 16) * j) * 8 + e;
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t lo = __builtin_amdgcn_perm(r[j * 4 + 1][e >> 1], r[j * 4 + 0][e >> 1], sel);
+        const uint32_t hi = __builtin_amdgcn_perm(r[j * 4 + 3][e >> 1], r[j * 4 + 2][e >> 1], sel);
+        *reinterpret_cast<uint2*>(lds_tile + row * ROWB + ((chunk ^ e) << 4) + half * 8) = make_uint2(lo, hi);
+      }
     }
   }
-}
+};
 
 __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row, int chunk) {
-  return *reinterpret_cast<const bf16x8_t*>(base + row * ROWB + ((chunk ^ (row & 7)) << 4));
+  return *reinterpret_cast<const bf16x8_t*>(base + row * ROWB + ((chunk ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
@@ -126,7 +141,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   constexpr int NW = WGM * WGN, NT = 64 * NW;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int STAGE = (BM + BN) * ROWB;
-  constexpr int RA = AKC ? 1 : BM * 2 / NT * 4, RB = BKC ? 1 : BN * 2 / NT * 4;
   static_assert(WN == 64 && (WM == 64 || WM == 128), "epilogue assumes 64-column wave tiles");
   static_assert(2 * STAGE >= NW * 16384, "epilogue needs 16 KiB of LDS per wave");
   extern __shared__ __align__(1024) unsigned char smem[];
@@ -180,76 +194,117 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4_t ra[RA], rb[RB];
+  // per-lane load offsets, fixed for the whole kernel (all segments share lda / ldb)
+  DirectLoader<BM, NW> dla;
+  DirectLoader<BN, NW> dlb;
+  TransposeLoader<BM, NT> tla;
+  TransposeLoader<BN, NT> tlb;
+  if constexpr (AKC) dla.init(p.lda[0], p.M - m0, wave, lane); else tla.init(p.lda[0], p.M - m0, tid);
+  if constexpr (BKC) dlb.init(p.ldb[0], p.N - n0, wave, lane); else tlb.init(p.ldb[0], p.N - n0, tid);
+  constexpr int NLA = AKC ? DirectLoader<BM, NW>::NL : TransposeLoader<BM, NT>::NL;
+  constexpr int NLB = BKC ? DirectLoader<BN, NW>::NL : TransposeLoader<BN, NT>::NL;
+  constexpr int NLT = NLA + NLB;
 
-  // start the loads of reduction tile kt (straight into LDS stage `stage` where possible)
-  auto issue = [&](int kt, int stage) {
-    int seg = 0;
-#pragma unroll
-    for (int s = 0; s < kMaxSeg - 1; ++s)
-      if (seg == s && kt >= nks[s]) {
-        kt -= nks[s];
-        seg = s + 1;
+  // cursor over the reduction tiles of all segments: operand pointers of the next tile to load
+  const int64_t stepA = AKC ? BK : (int64_t)BK * p.lda[0], stepB = BKC ? BK : (int64_t)BK * p.ldb[0];
+  const int64_t offA = AKC ? (int64_t)m0 * p.lda[0] : m0, offB = BKC ? (int64_t)n0 * p.ldb[0] : n0;
+  int cseg = 0, ck_left = kend0 - kbeg0;
+  const uint16_t* cA = p.A[0] + (int64_t)batch * p.sA[0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
+  const uint16_t* cB = p.B[0] + (int64_t)batch * p.sB[0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
+  auto advance = [&]() {
+    cA += stepA;
+    cB += stepB;
+    ck_left -= BK;
+    if (ck_left <= 0) {
+      do { ++cseg; } while (cseg < kMaxSeg && p.K[cseg] <= 0);
+      if (cseg < kMaxSeg) {
+        cA = p.A[cseg] + (int64_t)batch * p.sA[cseg] + offA;
+        cB = p.B[cseg] + (int64_t)batch * p.sB[cseg] + offB;
+        ck_left = p.K[cseg];
       }
-    const int k0 = (seg == 0 ? kbeg0 : 0) + kt * BK;
-    const int k_left = (seg == 0 ? kend0 : p.K[seg]) - k0;
-    const uint16_t* A = p.A[seg] + (int64_t)batch * p.sA[seg];
-    const uint16_t* B = p.B[seg] + (int64_t)batch * p.sB[seg];
-    const int64_t lda = p.lda[seg], ldb = p.ldb[seg];
+    }
+  };
+  // loads [l0, l1) of the tile under the cursor into LDS stage `stage` (or registers)
+  auto issue = [&](int stage, int l0, int l1) {
+    const __amdgpu_buffer_rsrc_t rsa = make_rsrc(cA), rsb = make_rsrc(cB);
     unsigned char* as = smem + stage * STAGE;
     unsigned char* bs = as + BM * ROWB;
-    if constexpr (AKC)
-      tile_load_direct<BM, NW>(A + (int64_t)m0 * lda + k0, lda, p.M - m0, k_left, as, wave, lane);
-    else
-      tile_load_regs<BM, NT>(ra, A + (int64_t)k0 * lda + m0, lda, p.M - m0, k_left, tid);
-    if constexpr (BKC)
-      tile_load_direct<BN, NW>(B + (int64_t)n0 * ldb + k0, ldb, p.N - n0, k_left, bs, wave, lane);
-    else
-      tile_load_regs<BN, NT>(rb, B + (int64_t)k0 * ldb + n0, ldb, p.N - n0, k_left, tid);
+#pragma unroll
+    for (int l = 0; l < NLT; ++l) {
+      if (l < l0 || l >= l1) continue;
+      if (l < NLA) {
+        if constexpr (AKC) dla.load(l, rsa, ck_left, as, wave); else tla.load(l, rsa, ck_left);
+      } else {
+        if constexpr (BKC) dlb.load(l - NLA, rsb, ck_left, bs, wave); else tlb.load(l - NLA, rsb, ck_left);
+      }
+    }
   };
-  // finish them: transposed operands go registers -> LDS here
+  // transposed operands: registers -> LDS
   auto commit = [&](int stage) {
     unsigned char* as = smem + stage * STAGE;
     unsigned char* bs = as + BM * ROWB;
-    if constexpr (!AKC) tile_store_transposed<BM, NT>(ra, as, tid);
-    if constexpr (!BKC) tile_store_transposed<BN, NT>(rb, bs, tid);
+    if constexpr (!AKC) tla.store(as, tid);
+    if constexpr (!BKC) tlb.store(bs, tid);
+  };
+  auto read_frags = [&](bf16x8_t (&af)[TM], bf16x8_t (&bfr)[TN], int stage, int kk) {
+    const unsigned char* as = smem + stage * STAGE;
+    const unsigned char* bs = as + BM * ROWB;
+    const int chunk = kk * 2 + (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[i] = frag_read(as, wm * WM + i * 32 + (lane & 31), chunk);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bfr[j] = frag_read(bs, wn * WN + j * 32 + (lane & 31), chunk);
   };
 
   if (nk > 0) {
-    issue(0, 0);
+    issue(0, 0, NLT);
+    advance();
     commit(0);
   }
   __builtin_amdgcn_s_waitcnt(0);  // this wave's direct loads have landed in LDS
   __syncthreads();
 
+  // Software pipeline: the fragments of step kk+1 are read from LDS while the MFMAs
+  // of step kk run, also across the tile boundary; the next tile's global loads
+  // are spread over the first three steps.
+  bf16x8_t af[2][TM], bfr[2][TN];
+  if (nk > 0) read_frags(af[0], bfr[0], 0, 0);
+  constexpr int KSTEPS = BK / 16;
+  constexpr int LPART = (NLT + KSTEPS - 2) / (KSTEPS - 1);
   for (int kt = 0; kt < nk; ++kt) {
     const bool more = kt + 1 < nk;
-    if (more) issue(kt + 1, (kt + 1) & 1);
-    const unsigned char* as = smem + (kt & 1) * STAGE;
-    const unsigned char* bs = as + BM * ROWB;
+    const int cur = kt & 1, nxt = cur ^ 1;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8_t af[TM], bfr[TN];
-      const int chunk = kk * 2 + (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = frag_read(as, wm * WM + i * 32 + (lane & 31), chunk);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[j] = frag_read(bs, wn * WN + j * 32 + (lane & 31), chunk);
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (kk < KSTEPS - 1) {
+#ifndef ASX_EXP_NOLOAD
+        if (more) issue(nxt, kk * LPART, (kk + 1) * LPART < NLT ? (kk + 1) * LPART : NLT);
+#endif
+        read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], cur, kk + 1);
+      } else {
+        if (more) {
+          commit(nxt);
+          advance();
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (more) read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], nxt, 0);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
     }
-    if (more) commit((kt + 1) & 1);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
   }
+  // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
   // --- epilogue.  MFMA 32x32 output: register r of lane l holds row
-  // 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.  Each wave stages 64 rows x
-  // 64 columns at a time through its own 16 KiB of LDS and reads them back as
+  // 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.  Each wave stages 32 rows x
+  // 64 columns at a time through its own slice of LDS (rows padded to 72 floats so
+  // that the two half-waves of a store hit different banks) and reads them back as
   // 4-column vectors (16 lanes per row), so the global accesses are row-contiguous.
+  constexpr int EP_LD = 72;
   float* stage_f = reinterpret_cast<float*>(smem + wave * 16384);
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
   const int vcol = (lane & 15) * 4, vrow = lane >> 4;
@@ -262,21 +317,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
       if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
   }
 #pragma unroll
-  for (int half = 0; half < TM / 2; ++half) {
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          stage_f[(i2 * 32 + (r >> 2) * 8 + row_l + (r & 3)) * 64 + j * 32 + col_l] = acc[half * 2 + i2][j][r];
+      for (int r = 0; r < 16; ++r)
+        stage_f[((r >> 2) * 8 + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
     __builtin_amdgcn_s_waitcnt(0);
 #pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < 8; ++it) {
       const int lr = it * 4 + vrow;
-      const int grow = m0 + wm * WM + half * 64 + lr;
+      const int grow = m0 + wm * WM + i * 32 + lr;
       if (grow >= p.M || gcol >= p.N) continue;
-      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * 64 + vcol);
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
       float v[4] = {v4[0], v4[1], v4[2], v4[3]};
       if (Pz) {
         float* dst = Pz + (int64_t)grow * p.N + gcol;
@@ -351,7 +404,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
         }
       }
     }
-    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next half overwrites the slice
+    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next 32 rows overwrite the slice
   }
 }
 
@@ -406,6 +459,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
       // 32-bit byte offsets inside one 256-row (or 64-reduction-row) tile
       if ((g.lda[s] & 7) || (g.ldb[s] & 7) || (g.sA[s] & 7) || (g.sB[s] & 7)) return hipErrorInvalidValue;
       if (g.lda[s] >= (1 << 22) || g.ldb[s] >= (1 << 22)) return hipErrorInvalidValue;
+      if (g.lda[s] != g.lda[0] || g.ldb[s] != g.ldb[0]) return hipErrorInvalidValue;  // one set of lane offsets
       if (!al16(g.A[s]) || !al16(g.B[s])) return hipErrorInvalidValue;
     }
   }
