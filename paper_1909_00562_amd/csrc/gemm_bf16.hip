@@ -269,6 +269,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   // are spread over the first three steps.
   bf16x8_t af[2][TM], bfr[2][TN];
   if (nk > 0) read_frags(af[0], bfr[0], 0, 0);
+#ifdef ASX_EXP_NOLDS
+  if (nk > 0) read_frags(af[1], bfr[1], 0, 1);
+#endif
   constexpr int KSTEPS = BK / 16;
   constexpr int LPART = (NLT + KSTEPS - 2) / (KSTEPS - 1);
   for (int kt = 0; kt < nk; ++kt) {
@@ -280,7 +283,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
 #ifndef ASX_EXP_NOLOAD
         if (more) issue(nxt, kk * LPART, (kk + 1) * LPART < NLT ? (kk + 1) * LPART : NLT);
 #endif
+#ifndef ASX_EXP_NOLDS
         read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], cur, kk + 1);
+#endif
       } else {
         if (more) {
           commit(nxt);
@@ -288,7 +293,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
+#ifndef ASX_EXP_NOLDS
         if (more) read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], nxt, 0);
+#endif
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)

@@ -212,7 +212,7 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split) 
   const int edge = bf16 ? 128 : FT;
   const int kt = bf16 ? 64 : FK;
   int64_t tiles = (int64_t)((M + edge - 1) / edge) * ((N + edge - 1) / edge) * batch;
-  if (bf16 && t256 >= 512) {
+  if (bf16 && t256 >= 512 && M >= 192 && N >= 192) {   // small M or N would waste most of a 256-row tile
     pl.big_tile = 1;
     return pl;
   }
