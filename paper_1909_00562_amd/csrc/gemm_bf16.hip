@@ -136,6 +136,121 @@ __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row
   return *reinterpret_cast<const bf16x8_t*>(base + row * ROWB + ((chunk ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
 }
 
+// ---- epilogue --------------------------------------------------------------------
+// MFMA 32x32 output: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4,
+// column l%32 of its tile.  Each wave stages 32 rows x 64 columns at a time through
+// its own slice of LDS (rows padded to 72 floats so that the two half-waves of a
+// store hit different banks) and reads them back as 4-column vectors (16 lanes per
+// row), so the global accesses are row-contiguous.  row0 / col0: first row / column
+// of this wave's tile in C.
+template <int TM, int TN, bool OUT_BF16>
+__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* smem,
+                                              int wave, int lane, int row0, int col0, int batch, int z) {
+  static_assert(TN == 2, "64-column wave tiles");
+  constexpr int EP_LD = 72;
+  float* stage_f = reinterpret_cast<float*>(smem + wave * 16384);
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  const int vcol = (lane & 15) * 4, vrow = lane >> 4;
+  const int gcol = col0 + vcol;
+  float* Pz = p.splits > 1 ? p.partial + (int64_t)z * p.M * p.N : nullptr;
+  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (p.bias && p.splits <= 1) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage_f[((r >> 2) * 8 + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
+    __builtin_amdgcn_s_waitcnt(0);
+#pragma unroll 4
+    for (int it = 0; it < 8; ++it) {
+      const int lr = it * 4 + vrow;
+      const int grow = row0 + i * 32 + lr;
+      if (grow >= p.M || gcol >= p.N) continue;
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
+      float v[4] = {v4[0], v4[1], v4[2], v4[3]};
+      if (Pz) {
+        float* dst = Pz + (int64_t)grow * p.N + gcol;
+        if (gcol + 3 < p.N && (p.N & 3) == 0) {
+          *reinterpret_cast<f32x4_t*>(dst) = v4;
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) dst[c] = v[c];
+        }
+        continue;
+      }
+      const bool vec = p.vec_ok && gcol + 3 < p.N;
+      const int64_t ci = (int64_t)batch * p.sC + (int64_t)grow * p.ldc + gcol;
+      float gt[4] = {1.f, 1.f, 1.f, 1.f};
+      if (p.gate) {
+        const float* gp = p.gate + (int64_t)grow * p.ldg + gcol;
+        if (vec) {
+          const f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(gp);
+          gt[0] = g4[0]; gt[1] = g4[1]; gt[2] = g4[2]; gt[3] = g4[3];
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) gt[c] = gp[c];
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float x = v[c] + bias4[c];
+        if (p.act_tanh) x = tanhf(x);
+        v[c] = x * gt[c];
+      }
+      if constexpr (OUT_BF16) {
+        uint16_t* C = reinterpret_cast<uint16_t*>(p.C) + ci;
+        uint32_t hb[4];
+        float lo[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          hb[c] = f32_to_bf16_bits(v[c]);
+          lo[c] = v[c] - bf16_bits_to_f32(hb[c]);
+        }
+        if (vec) {
+          *reinterpret_cast<uint2*>(C) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
+          if (p.C_lo)
+            *reinterpret_cast<uint2*>(p.C_lo + ci) = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
+          if (p.C_dact) {
+            f32x4_t d4 = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
+            *reinterpret_cast<f32x4_t*>(p.C_dact + ci) = d4;
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) {
+              C[c] = (uint16_t)hb[c];
+              if (p.C_lo) p.C_lo[ci + c] = (uint16_t)f32_to_bf16_bits(lo[c]);
+              if (p.C_dact) p.C_dact[ci + c] = 1.f - v[c] * v[c];
+            }
+        }
+      } else {
+        float* C = reinterpret_cast<float*>(p.C) + ci;
+        if (vec) {
+          if (p.accumulate) {
+            const f32x4_t o4 = *reinterpret_cast<const f32x4_t*>(C);
+            v[0] += o4[0]; v[1] += o4[1]; v[2] += o4[2]; v[3] += o4[3];
+          }
+          f32x4_t s4 = {v[0], v[1], v[2], v[3]};
+          *reinterpret_cast<f32x4_t*>(C) = s4;
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (gcol + c < p.N) C[c] = p.accumulate ? v[c] + C[c] : v[c];
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next 32 rows overwrite the slice
+  }
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   constexpr int NW = WGM * WGN, NT = 64 * NW;
@@ -306,113 +421,259 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   }
   // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
-  // --- epilogue.  MFMA 32x32 output: register r of lane l holds row
-  // 8*(r/4) + 4*(l/32) + r%4, column l%32 of its tile.  Each wave stages 32 rows x
-  // 64 columns at a time through its own slice of LDS (rows padded to 72 floats so
-  // that the two half-waves of a store hit different banks) and reads them back as
-  // 4-column vectors (16 lanes per row), so the global accesses are row-contiguous.
-  constexpr int EP_LD = 72;
-  float* stage_f = reinterpret_cast<float*>(smem + wave * 16384);
-  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
-  const int vcol = (lane & 15) * 4, vrow = lane >> 4;
-  const int gcol = n0 + wn * WN + vcol;
-  float* Pz = p.splits > 1 ? p.partial + (int64_t)z * p.M * p.N : nullptr;
-  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
-  if (p.bias && p.splits <= 1) {
+  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem, wave, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
+}
+
+
+// ---- 256x256 tile, 8 waves, two staggered wave groups ("ping-pong") ---------------
+// Reduction tiles of 64 elements, two LDS stages, every operand loaded HBM -> LDS
+// directly whatever its orientation:
+//   * reduction-contiguous operand: LDS tile [256 rows][64 k] (128-byte rows, chunks
+//     swizzled as above), fragments read with ds_read_b128;
+//   * strided-reduction operand: LDS tile [64 k][256 columns] exactly as in memory
+//     (512-byte rows, 64-byte segments XOR-swizzled with k & 3), fragments read with
+//     the transposing ds_read_b64_tr_b16: a 16-lane group presents four k-rows x 16
+//     columns and each lane receives four consecutive k of its own column.
+// Waves 0-3 (group A) and 4-7 (group B) sit pairwise on the four SIMDs.  Per tile a
+// wave alternates memory and compute phases,
+//     M0: read the fragments of steps 0,1      C0: 16 MFMAs from registers
+//     M1: read the fragments of steps 2,3      C1: 16 MFMAs
+// and there is ONE workgroup barrier per tile, which group A takes after its C1 and
+// group B after its M1: B therefore runs one phase behind A, so on every SIMD one
+// wave issues MFMAs while its partner waits on LDS, issues loads or sits at the
+// barrier, and the matrix pipe stays fed.
+// Hazards: tile t lives in stage t&1 and is read only between barrier t and barrier
+// t+1 (A: M0,M1 of its iteration t; B: likewise, its C1(t) needs registers only).
+// The loads of tile t+1 are issued right after barrier t into the stage tile t-1
+// has left, and every wave waits for its own loads before barrier t+1.
+constexpr int PTILE = 256 * BK * 2;   // bytes of one operand tile
+constexpr int PSTAGE = 2 * PTILE;
+
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+
+// wave-wide direct loads of one operand tile: 32 loads of 1 KiB per tile, four per wave
+template <bool KC>
+struct PpLoader {
+  uint32_t voff[4];
+  int kpos;   // KC: first reduction element of the lane's chunk; strided: its k-row for load 0
+  __device__ __forceinline__ void init(int64_t ld, int rows_left, int wave, int lane) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
+    for (int j = 0; j < 4; ++j) {
+      const int g = wave + 8 * j;
+      if constexpr (KC) {
+        // group g = rows 8g .. 8g+7; LDS slot `lane` = row lane/8, physical chunk lane%8
+        const int row = g * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ (lane >> 3) ^ (wave & 1);   // (row & 7) ^ ((row >> 3) & 1)
+        if (j == 0) kpos = chunk * 8;
+        voff[j] = row < rows_left ? (uint32_t)(((int64_t)row * ld + chunk * 8) * 2) : kOob;
+      } else {
+        // group g = k-rows 2g, 2g+1; LDS slot `lane` = k-row lane/32, physical 16-byte chunk lane%32
+        const int k = 2 * g + (lane >> 5);
+        const int pc = lane & 31;
+        const int seg = (pc >> 2) ^ (((wave & 1) << 1) + (lane >> 5));   // physical ^ (k & 3)
+        const int col = (seg * 4 + (pc & 3)) * 8;
+        if (j == 0) kpos = k;                                      // load j covers k-row kpos + 16 j
+        voff[j] = col < rows_left ? (uint32_t)(((int64_t)k * ld + col) * 2) : kOob;
+      }
+    }
   }
+  __device__ __forceinline__ void load_one(int j, const __amdgpu_buffer_rsrc_t& rs, int k_left,
+                                           unsigned char* lds_tile, int wave) const {
+    const bool ok = KC ? kpos < k_left : kpos + 16 * j < k_left;
+    const uint32_t off = ok ? voff[j] : kOob;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + (wave + 8 * j) * 1024), 16, off, 0, 0, 0);
+  }
+  __device__ __forceinline__ void load(const __amdgpu_buffer_rsrc_t& rs, int k_left, unsigned char* lds_tile,
+                                       int wave) const {
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+    for (int j = 0; j < 4; ++j) load_one(j, rs, k_left, lds_tile, wave);
+  }
+};
+
+// MFMA fragment (8 consecutive k of one row / column) of reduction step kk (0..3)
+template <bool KC>
+__device__ __forceinline__ bf16x8_t pp_frag(const unsigned char* tile, int row0, int kk, int lane) {
+  if constexpr (KC) {
+    return frag_read(tile, row0 + (lane & 31), kk * 2 + (lane >> 5));
+  } else {
+    const int col = row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;   // four columns this lane presents
+    const int kb = kk * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const int cb = col * 2;
+    union { s16x4_t h[2]; bf16x8_t v; } u;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int k = kb + q * 4;
+      const unsigned char* a = tile + k * 512 + ((((cb >> 6) ^ (k & 3))) << 6) + (cb & 63);
+      u.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(lds_void_t*)a);
+    }
+    return u.v;
+  }
+}
+
+template <bool AKC, bool BKC, bool OUT_BF16>
+__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p) {
+  constexpr int BM = 256, BN = 256, WGN = 4;
+  constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
+  extern __shared__ __align__(1024) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const bool groupB = wave >= 4;
+
+  const int nt = p.tiles_m * p.tiles_n;
+  int pid = blockIdx.x;
+  {
+    const int xcd = pid & 7, idx = pid >> 3;
+    const int per = nt >> 3, rem = nt & 7;
+    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
+  }
+  constexpr int GROUP = 8;
+  const int gsize = GROUP * p.tiles_n;
+  const int gid = pid / gsize;
+  const int first_m = gid * GROUP;
+  const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
+  const int in_g = pid - gid * gsize;
+  const int tile_m = first_m + in_g % gm, tile_n = in_g / gm;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int z = blockIdx.z;
+  const int batch = z / p.splits, split = z - batch * p.splits;
+  int kbeg0 = 0, kend0 = p.K[0];
+  if (p.splits > 1) {
+    kbeg0 = split * p.kper;
+    kend0 = kbeg0 + p.kper < p.K[0] ? kbeg0 + p.kper : p.K[0];
+  }
+  int nk = kend0 > kbeg0 ? (kend0 - kbeg0 + BK - 1) / BK : 0;
+#pragma unroll
+  for (int s = 1; s < kMaxSeg; ++s) nk += (p.K[s] + BK - 1) / BK;
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage_f[((r >> 2) * 8 + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
-    __builtin_amdgcn_s_waitcnt(0);
-#pragma unroll 4
-    for (int it = 0; it < 8; ++it) {
-      const int lr = it * 4 + vrow;
-      const int grow = m0 + wm * WM + i * 32 + lr;
-      if (grow >= p.M || gcol >= p.N) continue;
-      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
-      float v[4] = {v4[0], v4[1], v4[2], v4[3]};
-      if (Pz) {
-        float* dst = Pz + (int64_t)grow * p.N + gcol;
-        if (gcol + 3 < p.N && (p.N & 3) == 0) {
-          *reinterpret_cast<f32x4_t*>(dst) = v4;
-        } else {
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gcol + c < p.N) dst[c] = v[c];
-        }
-        continue;
-      }
-      const bool vec = p.vec_ok && gcol + 3 < p.N;
-      const int64_t ci = (int64_t)batch * p.sC + (int64_t)grow * p.ldc + gcol;
-      float gt[4] = {1.f, 1.f, 1.f, 1.f};
-      if (p.gate) {
-        const float* gp = p.gate + (int64_t)grow * p.ldg + gcol;
-        if (vec) {
-          const f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(gp);
-          gt[0] = g4[0]; gt[1] = g4[1]; gt[2] = g4[2]; gt[3] = g4[3];
-        } else {
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gcol + c < p.N) gt[c] = gp[c];
-        }
-      }
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        float x = v[c] + bias4[c];
-        if (p.act_tanh) x = tanhf(x);
-        v[c] = x * gt[c];
-      }
-      if constexpr (OUT_BF16) {
-        uint16_t* C = reinterpret_cast<uint16_t*>(p.C) + ci;
-        uint32_t hb[4];
-        float lo[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          hb[c] = f32_to_bf16_bits(v[c]);
-          lo[c] = v[c] - bf16_bits_to_f32(hb[c]);
-        }
-        if (vec) {
-          *reinterpret_cast<uint2*>(C) = make_uint2(hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16));
-          if (p.C_lo)
-            *reinterpret_cast<uint2*>(p.C_lo + ci) = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
-          if (p.C_dact) {
-            f32x4_t d4 = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
-            *reinterpret_cast<f32x4_t*>(p.C_dact + ci) = d4;
-          }
-        } else {
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gcol + c < p.N) {
-              C[c] = (uint16_t)hb[c];
-              if (p.C_lo) p.C_lo[ci + c] = (uint16_t)f32_to_bf16_bits(lo[c]);
-              if (p.C_dact) p.C_dact[ci + c] = 1.f - v[c] * v[c];
-            }
-        }
-      } else {
-        float* C = reinterpret_cast<float*>(p.C) + ci;
-        if (vec) {
-          if (p.accumulate) {
-            const f32x4_t o4 = *reinterpret_cast<const f32x4_t*>(C);
-            v[0] += o4[0]; v[1] += o4[1]; v[2] += o4[2]; v[3] += o4[3];
-          }
-          f32x4_t s4 = {v[0], v[1], v[2], v[3]};
-          *reinterpret_cast<f32x4_t*>(C) = s4;
-        } else {
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (gcol + c < p.N) C[c] = p.accumulate ? v[c] + C[c] : v[c];
-        }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  PpLoader<AKC> la;
+  PpLoader<BKC> lb;
+  la.init(p.lda[0], p.M - m0, wave, lane);
+  lb.init(p.ldb[0], p.N - n0, wave, lane);
+
+  // cursor over the reduction tiles of all segments: operands of the next tile to load
+  const int64_t stepA = AKC ? BK : (int64_t)BK * p.lda[0], stepB = BKC ? BK : (int64_t)BK * p.ldb[0];
+  const int64_t offA = AKC ? (int64_t)m0 * p.lda[0] : m0, offB = BKC ? (int64_t)n0 * p.ldb[0] : n0;
+  int cseg = 0, ck_left = kend0 - kbeg0;
+  const uint16_t* cA = p.A[0] + (int64_t)batch * p.sA[0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
+  const uint16_t* cB = p.B[0] + (int64_t)batch * p.sB[0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
+  auto advance = [&]() {
+#ifndef ASX_EXP_SAMETILE
+    cA += stepA;
+    cB += stepB;
+    ck_left -= BK;
+#endif
+    if (ck_left <= 0) {
+      do { ++cseg; } while (cseg < kMaxSeg && p.K[cseg] <= 0);
+      if (cseg < kMaxSeg) {
+        cA = p.A[cseg] + (int64_t)batch * p.sA[cseg] + offA;
+        cB = p.B[cseg] + (int64_t)batch * p.sB[cseg] + offB;
+        ck_left = p.K[cseg];
       }
     }
-    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next 32 rows overwrite the slice
+  };
+  auto issue = [&](int stage) {   // all loads of the tile under the cursor at once (prologue)
+    unsigned char* as = smem + stage * PSTAGE;
+    la.load(make_rsrc(cA), ck_left, as, wave);
+    lb.load(make_rsrc(cB), ck_left, as + PTILE, wave);
+    advance();
+  };
+  bf16x8_t af[2][TM], bfr[2][TN];
+  auto read_pair = [&](int stage, int kk0) {   // fragments of steps kk0, kk0+1
+    const unsigned char* as = smem + stage * PSTAGE;
+    const unsigned char* bs = as + PTILE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {   // in the order the MFMAs consume them
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag<BKC>(bs, wn * WN + j * 32, kk0 + h, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[h][i] = pp_frag<AKC>(as, wm * WM + i * 32, kk0 + h, lane);
+    }
+  };
+  // 16 MFMAs from registers; if `doload`, the eight loads of the tile under the cursor
+  // are issued between them (one per two MFMAs, so the address unit never backs up
+  // and no wave stalls in a burst of loads) into LDS stage `stage`
+  auto mfma_pair = [&](bool doload, int stage) {
+    unsigned char* as = smem + stage * PSTAGE;
+    const __amdgpu_buffer_rsrc_t rsa = make_rsrc(cA), rsb = make_rsrc(cB);
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
+          if (j == 1) {
+            const int slot = h * TM + i;   // 0..7
+            if (doload) {
+              if (slot < 4) la.load_one(slot, rsa, ck_left, as, wave);
+              else lb.load_one(slot - 4, rsb, ck_left, as + PTILE, wave);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (doload) advance();
+  };
+  auto tile_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr int WAIT_ALL = 0;        // s_waitcnt vmcnt(0) expcnt(0) lgkmcnt(0)
+  constexpr int WAIT_LGKM = 0xC07F;  // s_waitcnt lgkmcnt(0)
+
+  if (nk > 0) issue(0);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+  tile_barrier();                                   // barrier 0
+  if (groupB && nk > 1) issue(1);                   // B's first compute phase comes too late for tile 1
+
+  // Both groups run the same M0 C0 M1 C1 sequence; only the position of the tile
+  // barrier differs, which keeps group B one phase behind group A.  Each group
+  // issues the next tile's loads inside its first compute phase after the barrier
+  // (A: C0, tile t+1; B: C1, tile t+2), when the stage they go to is free.
+  for (int t = 0; t < nk; ++t) {
+    const int cur = t & 1, nxt = cur ^ 1;
+#ifndef ASX_EXP_NOLDS
+    read_pair(cur, 0);                              // M0
+#endif
+#ifndef ASX_EXP_NOLOAD
+    mfma_pair(!groupB && t + 1 < nk, nxt);          // C0 (+ A: loads of tile t+1)
+#else
+    mfma_pair(false, nxt);
+#endif
+#ifndef ASX_EXP_NOLDS
+    read_pair(cur, 2);                              // M1
+#endif
+    if (groupB) {
+      __builtin_amdgcn_s_waitcnt(WAIT_ALL);         // fragments in registers, own loads of tile t+1 landed
+      tile_barrier();                               // barrier t+1: every wave is done reading stage cur
+    }
+#ifndef ASX_EXP_NOLOAD
+    mfma_pair(groupB && t + 2 < nk, cur);           // C1 (+ B: loads of tile t+2 into the stage just freed)
+#else
+    mfma_pair(false, cur);
+#endif
+    if (!groupB) {
+      __builtin_amdgcn_s_waitcnt(WAIT_ALL);         // own loads of tile t+1 landed
+      tile_barrier();                               // barrier t+1
+    }
   }
+
+  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem, wave, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
@@ -429,6 +690,30 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   dim3 grid(d.tiles_m * d.tiles_n, 1, batch * d.splits);
   hipLaunchKernelGGL(kfn, grid, dim3(64 * WGM * WGN), smem, st, d);
   return hipGetLastError();
+}
+
+template <bool AKC, bool BKC, bool OUT_BF16>
+static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
+  constexpr int smem = 2 * PSTAGE;
+  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  dim3 grid(d.tiles_m * d.tiles_n, 1, batch * d.splits);
+  hipLaunchKernelGGL(kfn, grid, dim3(512), smem, st, d);
+  return hipGetLastError();
+}
+
+static hipError_t launch_big(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
+  const bool obf = g.c_bf16 && g.splits <= 1;
+  if (g.a_kc && g.b_kc) return obf ? launch_pp<true, true, true>(d, g.batch, st) : launch_pp<true, true, false>(d, g.batch, st);
+  if (g.a_kc && !g.b_kc) return obf ? launch_pp<true, false, true>(d, g.batch, st) : launch_pp<true, false, false>(d, g.batch, st);
+  if (!g.a_kc && !g.b_kc) return obf ? launch_pp<false, false, true>(d, g.batch, st) : launch_pp<false, false, false>(d, g.batch, st);
+  return hipErrorInvalidValue;
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -494,7 +779,11 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   const int ktiles = (g.K[0] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
+#ifdef ASX_NO_PINGPONG
   return big_tile ? launch_tile<256, 256, 2, 4>(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
+#else
+  return big_tile ? launch_big(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
+#endif
 }
 
 }  // namespace asx
