@@ -204,27 +204,59 @@ hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st
 }
 
 // ---- planner ----------------------------------------------------------------
+// Cost model (seconds) used to pick the block tile and the reduction split of a bf16
+// product on a 256-CU part: blocks run in rounds of `slots` (one 256x256 block or
+// two 128x128 blocks per CU); a round costs the block's flops at the per-CU rate
+// the kernel sustains plus a fixed prologue/epilogue; a split adds the round trip
+// of its fp32 partial sums through HBM and one more launch.
+static double plan_cost(int M, int N, int K, int batch, int tile, int splits) {
+  const double cus = 256.0;
+  const double rate = tile == 256 ? 3.9e12 : 1.35e12;      // flop/s of one resident block
+  const double slots = tile == 256 ? cus : 2.0 * cus;
+  const double fixed = tile == 256 ? 8e-6 : 5e-6;
+  const double blocks = (double)((M + tile - 1) / tile) * ((N + tile - 1) / tile) * batch * splits;
+  const double rounds = (double)(int64_t)((blocks + slots - 1) / slots);
+  const double kblk = (double)((K + splits - 1) / splits);
+  double t = rounds * (2.0 * tile * tile * kblk / rate + fixed);
+  if (splits > 1) t += 2.0 * splits * (double)M * N * batch * 4.0 / 4e12 + 8e-6;
+  return t;
+}
+
 GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split) {
   GemmPlan pl;
   pl.big_tile = 0;
   pl.splits = 1;
-  const int64_t t256 = (int64_t)((M + 255) / 256) * ((N + 255) / 256) * batch;
-  const int edge = bf16 ? 128 : FT;
-  const int kt = bf16 ? 64 : FK;
-  int64_t tiles = (int64_t)((M + edge - 1) / edge) * ((N + edge - 1) / edge) * batch;
-  if (bf16 && t256 >= 512 && M >= 192 && N >= 192) {   // small M or N would waste most of a 256-row tile
-    pl.big_tile = 1;
+  if (!bf16) {
+    // fp32 path: plain 64x64 tiles; split only to fill the machine
+    const int64_t tiles = (int64_t)((M + FT - 1) / FT) * ((N + FT - 1) / FT) * batch;
+    if (allow_split && tiles < 384) {
+      const int ktiles = (K + FK - 1) / FK;
+      int64_t want = (768 + tiles - 1) / tiles;
+      const int64_t cap = ktiles / 16;
+      if (want > cap) want = cap;
+      if (want > 32) want = 32;
+      if (want > 1) {
+        const int per = (int)((ktiles + want - 1) / want);
+        pl.splits = (ktiles + per - 1) / per;
+      }
+    }
     return pl;
   }
-  if (allow_split && tiles < 384) {
-    const int ktiles = (K + kt - 1) / kt;
-    int64_t want = (768 + tiles - 1) / tiles;
-    int64_t cap = ktiles / 4;            // at least 4 reduction tiles per split
-    if (want > cap) want = cap;
-    if (want > 32) want = 32;
-    if (want > 1) {
-      const int per = (int)((ktiles + want - 1) / want);
-      pl.splits = (ktiles + per - 1) / per;   // no empty split
+  const int ktiles = (K + 63) / 64;
+  double best = 1e30;
+  for (int tile = 128; tile <= 256; tile += 128) {
+    if (tile == 256 && (M < 192 || N < 192)) continue;   // most of a 256-row tile would be padding
+    const int smax = allow_split ? (ktiles / 4 < 32 ? (ktiles / 4 > 1 ? ktiles / 4 : 1) : 32) : 1;
+    for (int want = 1; want <= smax; ++want) {
+      const int per = (ktiles + want - 1) / want;
+      const int s = (ktiles + per - 1) / per;            // no empty split
+      if (s != want) continue;
+      const double c = plan_cost(M, N, K, batch, tile, s);
+      if (c < best) {
+        best = c;
+        pl.big_tile = tile == 256;
+        pl.splits = s;
+      }
     }
   }
   return pl;
