@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device-to-device copy kernel (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the path on ONE GPU only (no collectives, no sharding); "
@@ -108,6 +111,14 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     lib.load_library()                                   # fails loudly if the HIP library is not built
+    if a.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+        return
 
     inp = make_inputs(a.workload, dtype=a.dtype)
     db = lib.DeviceBatch(inp)
