@@ -143,12 +143,14 @@ __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row
 // store hit different banks) and reads them back as 4-column vectors (16 lanes per
 // row), so the global accesses are row-contiguous.  row0 / col0: first row / column
 // of this wave's tile in C.
-template <int TM, int TN, bool OUT_BF16>
-__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* smem,
-                                              int wave, int lane, int row0, int col0, int batch, int z) {
+// `region` is this wave's private LDS slice: CH rows of EP_LD floats (CH = 32 or 16).
+template <int TM, int TN, bool OUT_BF16, int CH = 32, int EP_LD = 72>
+__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
+                                              int lane, int row0, int col0, int batch, int z) {
   static_assert(TN == 2, "64-column wave tiles");
-  constexpr int EP_LD = 72;
-  float* stage_f = reinterpret_cast<float*>(smem + wave * 16384);
+  static_assert(CH == 32 || CH == 16, "chunk of one or half an MFMA tile");
+  constexpr int WAIT_LGKM_ONLY = 0xC07F;   // leaves global loads in flight
+  float* stage_f = reinterpret_cast<float*>(region);
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
   const int vcol = (lane & 15) * 4, vrow = lane >> 4;
   const int gcol = col0 + vcol;
@@ -160,17 +162,21 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
       if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
   }
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
+  for (int ic = 0; ic < TM * (32 / CH); ++ic) {
+    const int i = ic / (32 / CH), part = ic % (32 / CH);   // MFMA tile row, chunk inside it
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage_f[((r >> 2) * 8 + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
-    __builtin_amdgcn_s_waitcnt(0);
+      for (int r = 0; r < 16; ++r) {
+        const int trow = (r >> 2) * 8;                      // 0, 8, 16, 24: row group of register r
+        if (trow / CH != part) continue;
+        stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
+      }
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
 #pragma unroll 4
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < CH / 4; ++it) {
       const int lr = it * 4 + vrow;
-      const int grow = row0 + i * 32 + lr;
+      const int grow = row0 + i * 32 + part * CH + lr;
       if (grow >= p.M || gcol >= p.N) continue;
       const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
       float v[4] = {v4[0], v4[1], v4[2], v4[3]};
@@ -247,7 +253,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
         }
       }
     }
-    __builtin_amdgcn_s_waitcnt(0);  // LDS reads done before the next 32 rows overwrite the slice
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);  // LDS reads done before the next rows overwrite the slice
   }
 }
 
@@ -384,9 +390,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   // are spread over the first three steps.
   bf16x8_t af[2][TM], bfr[2][TN];
   if (nk > 0) read_frags(af[0], bfr[0], 0, 0);
-#ifdef ASX_EXP_NOLDS
-  if (nk > 0) read_frags(af[1], bfr[1], 0, 1);
-#endif
   constexpr int KSTEPS = BK / 16;
   constexpr int LPART = (NLT + KSTEPS - 2) / (KSTEPS - 1);
   for (int kt = 0; kt < nk; ++kt) {
@@ -395,12 +398,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
       if (kk < KSTEPS - 1) {
-#ifndef ASX_EXP_NOLOAD
         if (more) issue(nxt, kk * LPART, (kk + 1) * LPART < NLT ? (kk + 1) * LPART : NLT);
-#endif
-#ifndef ASX_EXP_NOLDS
         read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], cur, kk + 1);
-#endif
       } else {
         if (more) {
           commit(nxt);
@@ -408,9 +407,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
         }
         __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
-#ifndef ASX_EXP_NOLDS
         if (more) read_frags(af[(kk + 1) & 1], bfr[(kk + 1) & 1], nxt, 0);
-#endif
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -421,7 +418,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   }
   // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
-  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem, wave, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
+  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
 }
 
 
@@ -444,8 +441,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
 // barrier, and the matrix pipe stays fed.
 // Hazards: tile t lives in stage t&1 and is read only between barrier t and barrier
 // t+1 (A: M0,M1 of its iteration t; B: likewise, its C1(t) needs registers only).
-// The loads of tile t+1 are issued right after barrier t into the stage tile t-1
-// has left, and every wave waits for its own loads before barrier t+1.
+// The loads of tile t+1 are issued after barrier t (in M0 of iteration t) into the
+// stage tile t-1 has left, and every wave waits for its own loads before barrier t+1.
 constexpr int PTILE = 256 * BK * 2;   // bytes of one operand tile
 constexpr int PSTAGE = 2 * PTILE;
 
@@ -491,28 +488,49 @@ struct PpLoader {
   }
 };
 
-// MFMA fragment (8 consecutive k of one row / column) of reduction step kk (0..3)
+// MFMA fragments (8 consecutive k of one row / column per lane).  The lane's byte
+// offset inside an operand tile is computed once per kernel (pp_frag_base); the
+// fragment of reduction step kk is then one XOR away (reduction-contiguous tiles: the
+// swizzled chunk index is chunk0 ^ (kk << 1)) or a constant offset away (strided
+// tiles: step kk starts 16 k-rows = 8 KiB further, and k & 3 does not depend on kk).
 template <bool KC>
-__device__ __forceinline__ bf16x8_t pp_frag(const unsigned char* tile, int row0, int kk, int lane) {
+__device__ __forceinline__ uint32_t pp_frag_base(int row0, int lane) {
   if constexpr (KC) {
-    return frag_read(tile, row0 + (lane & 31), kk * 2 + (lane >> 5));
+    const int row = row0 + (lane & 31);
+    const int chunk0 = (lane >> 5) ^ (row & 7) ^ ((row >> 3) & 1);
+    return (uint32_t)(row * ROWB + (chunk0 << 4));
   } else {
     const int col = row0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4;   // four columns this lane presents
-    const int kb = kk * 16 + (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const int kq = (lane & 15) >> 2;                                   // k & 3 of every row it reads
+    const int k0 = (lane >> 5) * 8 + kq;
     const int cb = col * 2;
+    return (uint32_t)(k0 * 512 + (((cb >> 6) ^ kq) << 6) + (cb & 63));
+  }
+}
+template <bool KC>
+__device__ __forceinline__ bf16x8_t pp_frag_at(const unsigned char* tile, uint32_t base, int kk) {
+  if constexpr (KC) {
+    return *reinterpret_cast<const bf16x8_t*>(tile + (base ^ (uint32_t)(kk << 5)));
+  } else {
     union { s16x4_t h[2]; bf16x8_t v; } u;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int k = kb + q * 4;
-      const unsigned char* a = tile + k * 512 + ((((cb >> 6) ^ (k & 3))) << 6) + (cb & 63);
-      u.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(lds_void_t*)a);
-    }
+    for (int q = 0; q < 2; ++q)
+      u.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(lds_void_t*)(tile + base + kk * 8192 + q * 2048));
     return u.v;
   }
 }
 
+// The kernel is persistent: the grid is one block per CU, and each block walks its
+// list of (output tile, reduction split, batch) work items as ONE stream of
+// reduction tiles, so the loads of the next item's first tiles are in flight while
+// the current item finishes and is written out (its epilogue stages through a
+// separate 32 KiB of LDS): no pipeline fill / drain and no launch gap per output tile.
+constexpr int PP_EPI_OFF = 2 * PSTAGE;        // epilogue staging behind the two tile stages
+constexpr int PP_SMEM = PP_EPI_OFF + 8 * 4096;
+
 template <bool AKC, bool BKC, bool OUT_BF16>
-__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p) {
+__global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_total) {
   constexpr int BM = 256, BN = 256, WGN = 4;
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
   extern __shared__ __align__(1024) unsigned char smem[];
@@ -522,111 +540,129 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p) {
   const int wm = wave / WGN, wn = wave % WGN;
   const bool groupB = wave >= 4;
 
+  // Work items are numbered z-major (z = batch * splits + split), tile-minor; consecutive
+  // blocks go round-robin to the 8 XCDs, so XCD x owns a contiguous run of items and
+  // its blocks take them interleaved: co-resident blocks work on neighbouring tiles and
+  // share operand panels in their XCD's L2.
   const int nt = p.tiles_m * p.tiles_n;
-  int pid = blockIdx.x;
-  {
-    const int xcd = pid & 7, idx = pid >> 3;
-    const int per = nt >> 3, rem = nt & 7;
-    pid = xcd * per + (xcd < rem ? xcd : rem) + idx;
-  }
-  constexpr int GROUP = 8;
-  const int gsize = GROUP * p.tiles_n;
-  const int gid = pid / gsize;
-  const int first_m = gid * GROUP;
-  const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
-  const int in_g = pid - gid * gsize;
-  const int tile_m = first_m + in_g % gm, tile_n = in_g / gm;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int xcd = blockIdx.x & 7, bidx = blockIdx.x >> 3, nbx = gridDim.x >> 3;
+  const int wper = work_total >> 3, wrem = work_total & 7;
+  const int wbeg = xcd * wper + (xcd < wrem ? xcd : wrem);
+  const int wend = wbeg + wper + (xcd < wrem ? 1 : 0);
 
-  const int z = blockIdx.z;
-  const int batch = z / p.splits, split = z - batch * p.splits;
-  int kbeg0 = 0, kend0 = p.K[0];
-  if (p.splits > 1) {
-    kbeg0 = split * p.kper;
-    kend0 = kbeg0 + p.kper < p.K[0] ? kbeg0 + p.kper : p.K[0];
-  }
-  int nk = kend0 > kbeg0 ? (kend0 - kbeg0 + BK - 1) / BK : 0;
+  struct Item {
+    int m0, n0, batch, z, kbeg, kend;
+  };
+  auto get_item = [&](int w) {   // w in [wbeg, wend)
+    Item it;
+    it.z = w / nt;
+    const int pid = w - it.z * nt;
+    constexpr int GROUP = 8;      // tiles are walked in groups of 8 tile rows
+    const int gsize = GROUP * p.tiles_n;
+    const int gid = pid / gsize;
+    const int first_m = gid * GROUP;
+    const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
+    const int in_g = pid - gid * gsize;
+    it.m0 = (first_m + in_g % gm) * BM;
+    it.n0 = (in_g / gm) * BN;
+    it.batch = it.z / p.splits;
+    const int split = it.z - it.batch * p.splits;
+    it.kbeg = 0;
+    it.kend = p.K[0];
+    if (p.splits > 1) {
+      it.kbeg = split * p.kper;
+      it.kend = it.kbeg + p.kper < p.K[0] ? it.kbeg + p.kper : p.K[0];
+    }
+    return it;
+  };
+  int nk_rest = 0;   // reduction tiles of all segments but the first
 #pragma unroll
-  for (int s = 1; s < kMaxSeg; ++s) nk += (p.K[s] + BK - 1) / BK;
+  for (int s = 1; s < kMaxSeg; ++s) nk_rest += (p.K[s] + BK - 1) / BK;
 
   f32x16_t acc[TM][TN];
+  auto zero_acc = [&]() {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  };
+  zero_acc();
 
+  // ---- load stream: cursor over (item, segment, reduction tile) --------------------
   PpLoader<AKC> la;
   PpLoader<BKC> lb;
-  la.init(p.lda[0], p.M - m0, wave, lane);
-  lb.init(p.ldb[0], p.N - n0, wave, lane);
-
-  // cursor over the reduction tiles of all segments: operands of the next tile to load
   const int64_t stepA = AKC ? BK : (int64_t)BK * p.lda[0], stepB = BKC ? BK : (int64_t)BK * p.ldb[0];
-  const int64_t offA = AKC ? (int64_t)m0 * p.lda[0] : m0, offB = BKC ? (int64_t)n0 * p.ldb[0] : n0;
-  int cseg = 0, ck_left = kend0 - kbeg0;
-  const uint16_t* cA = p.A[0] + (int64_t)batch * p.sA[0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
-  const uint16_t* cB = p.B[0] + (int64_t)batch * p.sB[0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
+  int lw = wbeg + bidx;        // work item the cursor is in
+  bool lvalid = lw < wend;     // false once every tile of this block has been issued
+  int cseg = 0, ck_left = 0;
+  const uint16_t *cA = nullptr, *cB = nullptr;
+  int64_t offA = 0, offB = 0;
+  int lbatch = 0;
+  auto enter_item = [&]() {    // cursor to the first reduction tile of item lw
+    const Item it = get_item(lw);
+    la.init(p.lda[0], p.M - it.m0, wave, lane);
+    lb.init(p.ldb[0], p.N - it.n0, wave, lane);
+    offA = AKC ? (int64_t)it.m0 * p.lda[0] : it.m0;
+    offB = BKC ? (int64_t)it.n0 * p.ldb[0] : it.n0;
+    lbatch = it.batch;
+    cseg = 0;
+    ck_left = it.kend - it.kbeg;
+    cA = p.A[0] + (int64_t)lbatch * p.sA[0] + offA + (AKC ? it.kbeg : (int64_t)it.kbeg * p.lda[0]);
+    cB = p.B[0] + (int64_t)lbatch * p.sB[0] + offB + (BKC ? it.kbeg : (int64_t)it.kbeg * p.ldb[0]);
+  };
   auto advance = [&]() {
-#ifndef ASX_EXP_SAMETILE
     cA += stepA;
     cB += stepB;
     ck_left -= BK;
-#endif
     if (ck_left <= 0) {
       do { ++cseg; } while (cseg < kMaxSeg && p.K[cseg] <= 0);
       if (cseg < kMaxSeg) {
-        cA = p.A[cseg] + (int64_t)batch * p.sA[cseg] + offA;
-        cB = p.B[cseg] + (int64_t)batch * p.sB[cseg] + offB;
+        cA = p.A[cseg] + (int64_t)lbatch * p.sA[cseg] + offA;
+        cB = p.B[cseg] + (int64_t)lbatch * p.sB[cseg] + offB;
         ck_left = p.K[cseg];
+      } else {
+        lw += nbx;
+        lvalid = lw < wend;
+        if (lvalid) enter_item();
       }
     }
   };
-  auto issue = [&](int stage) {   // all loads of the tile under the cursor at once (prologue)
+  auto issue = [&](int stage) {   // this wave's eight loads of the tile under the cursor
     unsigned char* as = smem + stage * PSTAGE;
     la.load(make_rsrc(cA), ck_left, as, wave);
     lb.load(make_rsrc(cB), ck_left, as + PTILE, wave);
     advance();
   };
   bf16x8_t af[2][TM], bfr[2][TN];
+  uint32_t abase[TM], bbase[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) abase[i] = pp_frag_base<AKC>(wm * WM + i * 32, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bbase[j] = pp_frag_base<BKC>(wn * WN + j * 32, lane);
   auto read_pair = [&](int stage, int kk0) {   // fragments of steps kk0, kk0+1
     const unsigned char* as = smem + stage * PSTAGE;
     const unsigned char* bs = as + PTILE;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {   // in the order the MFMAs consume them
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag<BKC>(bs, wn * WN + j * 32, kk0 + h, lane);
+      for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag_at<BKC>(bs, bbase[j], kk0 + h);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[h][i] = pp_frag<AKC>(as, wm * WM + i * 32, kk0 + h, lane);
+      for (int i = 0; i < TM; ++i) af[h][i] = pp_frag_at<AKC>(as, abase[i], kk0 + h);
     }
   };
-  // 16 MFMAs from registers; if `doload`, the eight loads of the tile under the cursor
-  // are issued between them (one per two MFMAs, so the address unit never backs up
-  // and no wave stalls in a burst of loads) into LDS stage `stage`
-  auto mfma_pair = [&](bool doload, int stage) {
-    unsigned char* as = smem + stage * PSTAGE;
-    const __amdgpu_buffer_rsrc_t rsa = make_rsrc(cA), rsb = make_rsrc(cB);
+  auto mfma_pair = [&]() {   // 16 MFMAs from the fragment registers
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
-          if (j == 1) {
-            const int slot = h * TM + i;   // 0..7
-            if (doload) {
-              if (slot < 4) la.load_one(slot, rsa, ck_left, as, wave);
-              else lb.load_one(slot - 4, rsb, ck_left, as + PTILE, wave);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }
-        }
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
-    if (doload) advance();
   };
   auto tile_barrier = [&]() {
     __builtin_amdgcn_sched_barrier(0);
@@ -634,46 +670,43 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p) {
     __builtin_amdgcn_sched_barrier(0);
   };
   constexpr int WAIT_ALL = 0;        // s_waitcnt vmcnt(0) expcnt(0) lgkmcnt(0)
-  constexpr int WAIT_LGKM = 0xC07F;  // s_waitcnt lgkmcnt(0)
 
-  if (nk > 0) issue(0);
+  if (!lvalid) return;               // more blocks than work items: nothing to do (whole block leaves)
+  enter_item();
+  issue(0);
   __builtin_amdgcn_s_waitcnt(WAIT_ALL);
   tile_barrier();                                   // barrier 0
-  if (groupB && nk > 1) issue(1);                   // B's first compute phase comes too late for tile 1
 
-  // Both groups run the same M0 C0 M1 C1 sequence; only the position of the tile
-  // barrier differs, which keeps group B one phase behind group A.  Each group
-  // issues the next tile's loads inside its first compute phase after the barrier
-  // (A: C0, tile t+1; B: C1, tile t+2), when the stage they go to is free.
-  for (int t = 0; t < nk; ++t) {
-    const int cur = t & 1, nxt = cur ^ 1;
-#ifndef ASX_EXP_NOLDS
-    read_pair(cur, 0);                              // M0
-#endif
-#ifndef ASX_EXP_NOLOAD
-    mfma_pair(!groupB && t + 1 < nk, nxt);          // C0 (+ A: loads of tile t+1)
-#else
-    mfma_pair(false, nxt);
-#endif
-#ifndef ASX_EXP_NOLDS
-    read_pair(cur, 2);                              // M1
-#endif
-    if (groupB) {
-      __builtin_amdgcn_s_waitcnt(WAIT_ALL);         // fragments in registers, own loads of tile t+1 landed
-      tile_barrier();                               // barrier t+1: every wave is done reading stage cur
+  // Both groups run the same M0 C0 M1 C1 sequence per reduction tile; only the position
+  // of the tile barrier differs, which keeps group B one phase behind group A.  Every
+  // wave issues its share of the next tile's loads in M0, behind its fragment reads:
+  // both groups are past barrier g there, so the stage tile g-1 has left is free, and
+  // the loads have the rest of the iteration to land while the partner wave computes.
+  int g = 0;                                        // reduction tiles done: stage parity
+  for (int cw = wbeg + bidx; cw < wend; cw += nbx) {
+    const Item it = get_item(cw);
+    const int nk = (it.kend - it.kbeg + BK - 1) / BK + nk_rest;
+    for (int t = 0; t < nk; ++t, ++g) {
+      const int cur = g & 1, nxt = cur ^ 1;
+      read_pair(cur, 0);                            // M0
+      if (lvalid) issue(nxt);
+      mfma_pair();                                  // C0
+      read_pair(cur, 2);                            // M1
+      if (groupB) {
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL);       // fragments in registers, own loads of the next tile landed
+        tile_barrier();                             // every wave is done reading stage cur
+      }
+      mfma_pair();                                  // C1
+      if (!groupB) {
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL);       // own loads of the next tile landed
+        tile_barrier();
+      }
     }
-#ifndef ASX_EXP_NOLOAD
-    mfma_pair(groupB && t + 2 < nk, cur);           // C1 (+ B: loads of tile t+2 into the stage just freed)
-#else
-    mfma_pair(false, cur);
-#endif
-    if (!groupB) {
-      __builtin_amdgcn_s_waitcnt(WAIT_ALL);         // own loads of tile t+1 landed
-      tile_barrier();                               // barrier t+1
-    }
+    // item done: write it out while the next item's first tile is already in flight
+    gemm_epilogue<TM, TN, OUT_BF16, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
+                                            it.n0 + wn * WN, it.batch, it.z);
+    zero_acc();
   }
-
-  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem, wave, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
 }
 
 template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
@@ -694,7 +727,7 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
 
 template <bool AKC, bool BKC, bool OUT_BF16>
 static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
-  constexpr int smem = 2 * PSTAGE;
+  constexpr int smem = PP_SMEM;
   auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -703,8 +736,10 @@ static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(d.tiles_m * d.tiles_n, 1, batch * d.splits);
-  hipLaunchKernelGGL(kfn, grid, dim3(512), smem, st, d);
+  // persistent: one block per CU (a multiple of the 8 XCDs), each walking its share of the work items
+  const int work_total = d.tiles_m * d.tiles_n * batch * d.splits;
+  int blocks = work_total < 256 ? (work_total + 7) / 8 * 8 : 256;
+  hipLaunchKernelGGL(kfn, dim3(blocks), dim3(512), smem, st, d, work_total);
   return hipGetLastError();
 }
 
@@ -779,11 +814,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   const int ktiles = (g.K[0] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
-#ifdef ASX_NO_PINGPONG
-  return big_tile ? launch_tile<256, 256, 2, 4>(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
-#else
   return big_tile ? launch_big(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
-#endif
 }
 
 }  // namespace asx
