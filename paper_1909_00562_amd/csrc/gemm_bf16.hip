@@ -449,15 +449,17 @@ constexpr int PSTAGE = 2 * PTILE;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
-// wave-wide direct loads of one operand tile: 32 loads of 1 KiB per tile, four per wave
-template <bool KC>
+// wave-wide direct loads of one operand tile: 32 loads of 1 KiB per tile, NL = 32 / NW per wave
+template <bool KC, int NW = 8>
 struct PpLoader {
-  uint32_t voff[4];
+  static constexpr int NL = 32 / NW;
+  static_assert(NW % 2 == 0, "the swizzle terms below take the parity of a row group from the wave index");
+  uint32_t voff[NL];
   int kpos;   // KC: first reduction element of the lane's chunk; strided: its k-row for load 0
   __device__ __forceinline__ void init(int64_t ld, int rows_left, int wave, int lane) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int g = wave + 8 * j;
+    for (int j = 0; j < NL; ++j) {
+      const int g = wave + NW * j;
       if constexpr (KC) {
         // group g = rows 8g .. 8g+7; LDS slot `lane` = row lane/8, physical chunk lane%8
         const int row = g * 8 + (lane >> 3);
@@ -470,21 +472,21 @@ struct PpLoader {
         const int pc = lane & 31;
         const int seg = (pc >> 2) ^ (((wave & 1) << 1) + (lane >> 5));   // physical ^ (k & 3)
         const int col = (seg * 4 + (pc & 3)) * 8;
-        if (j == 0) kpos = k;                                      // load j covers k-row kpos + 16 j
+        if (j == 0) kpos = k;                                      // load j covers k-row kpos + 2 NW j
         voff[j] = col < rows_left ? (uint32_t)(((int64_t)k * ld + col) * 2) : kOob;
       }
     }
   }
   __device__ __forceinline__ void load_one(int j, const __amdgpu_buffer_rsrc_t& rs, int k_left,
                                            unsigned char* lds_tile, int wave) const {
-    const bool ok = KC ? kpos < k_left : kpos + 16 * j < k_left;
+    const bool ok = KC ? kpos < k_left : kpos + 2 * NW * j < k_left;
     const uint32_t off = ok ? voff[j] : kOob;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + (wave + 8 * j) * 1024), 16, off, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + (wave + NW * j) * 1024), 16, off, 0, 0, 0);
   }
   __device__ __forceinline__ void load(const __amdgpu_buffer_rsrc_t& rs, int k_left, unsigned char* lds_tile,
                                        int wave) const {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) load_one(j, rs, k_left, lds_tile, wave);
+    for (int j = 0; j < NL; ++j) load_one(j, rs, k_left, lds_tile, wave);
   }
 };
 
