@@ -144,11 +144,114 @@ __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row
 // row), so the global accesses are row-contiguous.  row0 / col0: first row / column
 // of this wave's tile in C.
 // `region` is this wave's private LDS slice: CH rows of EP_LD floats (CH = 32 or 16).
-template <int TM, int TN, bool OUT_BF16, int CH = 32, int EP_LD = 72>
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+// Vector form of the epilogue below for products whose destinations allow 8/16-byte
+// row vectors and whose N is a multiple of 4 (chosen on the host, per launch): stores (and the gate / accumulate
+// loads) go through buffer resources that start at the wave tile's first element, so
+// the row part of an address is a scalar offset, the lane part one register, and rows
+// beyond M are dropped by pointing the lane offset outside the resource instead of branching.
+template <int TM, int TN, bool OUT_BF16, int CH, int EP_LD>
+__device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
+                                                  int lane, int row0, int col0, int batch, int z) {
+  constexpr int WAIT_LGKM_ONLY = 0xC07F;
+  constexpr int ES = OUT_BF16 ? 2 : 4;
+  float* stage_f = reinterpret_cast<float*>(region);
+  const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+  const int vcol = (lane & 15) * 4, vrow = lane >> 4;
+  const bool to_partial = p.splits > 1;
+  const int64_t ld = to_partial ? (int64_t)p.N : p.ldc;
+  const int64_t origin = to_partial ? ((int64_t)z * p.M + row0) * p.N + col0
+                                    : (int64_t)batch * p.sC + (int64_t)row0 * p.ldc + col0;
+  unsigned char* cbase = to_partial ? reinterpret_cast<unsigned char*>(p.partial) : reinterpret_cast<unsigned char*>(p.C);
+  const __amdgpu_buffer_rsrc_t rs_c = make_rsrc(cbase + origin * ES);
+  const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(p.C_lo ? p.C_lo + origin : nullptr);
+  const __amdgpu_buffer_rsrc_t rs_da = make_rsrc(p.C_dact ? p.C_dact + origin : nullptr);
+  const float* gate0 = p.gate ? p.gate + (int64_t)row0 * p.ldg + col0 : nullptr;   // gate and old-C reads: plain loads
+  const int rows_left = p.M - row0 - vrow;                       // rows of C from this lane's first row on
+  const bool col_in = col0 + vcol < p.N;                         // N % 4 == 0: a 4-column group is all in or all out
+  const uint32_t lane_off = (uint32_t)(vrow * ld + vcol);        // elements, inside the wave tile's window
+  const uint32_t lane_off_g = (uint32_t)(vrow * p.ldg + vcol);
+  const uint32_t ld32 = (uint32_t)ld, ldg32 = (uint32_t)p.ldg;
+  const bool fuse = !to_partial;
+  float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+  if (p.bias && fuse) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (col_in) bias4[c] = bf16_bits_to_f32(p.bias[col0 + vcol + c]);
+  }
+#pragma unroll
+  for (int ic = 0; ic < TM * (32 / CH); ++ic) {
+    const int i = ic / (32 / CH), part = ic % (32 / CH);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int trow = (r >> 2) * 8;
+        if (trow / CH != part) continue;
+        stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
+      }
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
+#pragma unroll
+    for (int it = 0; it < CH / 4; ++it) {
+      const int nrow = i * 32 + part * CH + it * 4;              // tile row of the lane's row group (compile time)
+      const bool in = nrow < rows_left && col_in;
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + (it * 4 + vrow) * EP_LD + vcol);
+      const uint32_t row_el = (uint32_t)nrow * ld32;             // wave-uniform: goes into the scalar offset operand
+      float v[4] = {v4[0] + bias4[0], v4[1] + bias4[1], v4[2] + bias4[2], v4[3] + bias4[3]};
+      if (fuse && p.act_tanh) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = tanhf(v[c]);
+      }
+      if (fuse && p.gate && in) {
+        const f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(gate0 + (uint32_t)nrow * ldg32 + lane_off_g);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] *= g4[c];
+      }
+      if constexpr (OUT_BF16) {
+        const uint32_t off = in ? lane_off * 2u : kOob;
+        uint32_t hb[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) hb[c] = f32_to_bf16_bits(v[c]);
+        const u32x2_t hv = {hb[0] | (hb[1] << 16), hb[2] | (hb[3] << 16)};
+        __builtin_amdgcn_raw_buffer_store_b64(hv, rs_c, off, row_el * 2u, 0);
+        if (p.C_lo) {
+          const u32x2_t lv = {pack_bf16(v[0] - bf16_bits_to_f32(hb[0]), v[1] - bf16_bits_to_f32(hb[1])),
+                              pack_bf16(v[2] - bf16_bits_to_f32(hb[2]), v[3] - bf16_bits_to_f32(hb[3]))};
+          __builtin_amdgcn_raw_buffer_store_b64(lv, rs_lo, off, row_el * 2u, 0);
+        }
+        if (p.C_dact) {
+          const u32x4_t dv = {__builtin_bit_cast(uint32_t, 1.f - v[0] * v[0]), __builtin_bit_cast(uint32_t, 1.f - v[1] * v[1]),
+                              __builtin_bit_cast(uint32_t, 1.f - v[2] * v[2]), __builtin_bit_cast(uint32_t, 1.f - v[3] * v[3])};
+          __builtin_amdgcn_raw_buffer_store_b128(dv, rs_da, in ? lane_off * 4u : kOob, row_el * 4u, 0);
+        }
+      } else {
+        const uint32_t off = in ? lane_off * 4u : kOob;
+        if (fuse && p.accumulate && in) {
+          const f32x4_t o4 =
+              *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(cbase) + origin + row_el + lane_off);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[c] += o4[c];
+        }
+        const u32x4_t sv = {__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
+                            __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
+        __builtin_amdgcn_raw_buffer_store_b128(sv, rs_c, off, row_el * 4u, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);           // keeps the live ranges of one row group apart from the next
+    }
+    __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);  // LDS reads done before the next rows overwrite the slice
+  }
+}
+
+template <int TM, int TN, bool OUT_BF16, bool VEC, int CH = 32, int EP_LD = 72>
 __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
                                               int lane, int row0, int col0, int batch, int z) {
   static_assert(TN == 2, "64-column wave tiles");
   static_assert(CH == 32 || CH == 16, "chunk of one or half an MFMA tile");
+  if constexpr (VEC) {
+    gemm_epilogue_vec<TM, TN, OUT_BF16, CH, EP_LD>(p, acc, region, lane, row0, col0, batch, z);
+    return;
+  }
   constexpr int WAIT_LGKM_ONLY = 0xC07F;   // leaves global loads in flight
   float* stage_f = reinterpret_cast<float*>(region);
   const int col_l = lane & 31, row_l = (lane >> 5) * 4;
@@ -257,7 +360,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   constexpr int NW = WGM * WGN, NT = 64 * NW;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
@@ -418,7 +521,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   }
   // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
-  gemm_epilogue<TM, TN, OUT_BF16>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
+  gemm_epilogue<TM, TN, OUT_BF16, VEC>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
 }
 
 
@@ -531,7 +634,7 @@ __device__ __forceinline__ bf16x8_t pp_frag_at(const unsigned char* tile, uint32
 constexpr int PP_EPI_OFF = 2 * PSTAGE;        // epilogue staging behind the two tile stages
 constexpr int PP_SMEM = PP_EPI_OFF + 8 * 4096;
 
-template <bool AKC, bool BKC, bool OUT_BF16>
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_total) {
   constexpr int BM = 256, BN = 256, WGN = 4;
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
@@ -705,16 +808,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
       }
     }
     // item done: write it out while the next item's first tile is already in flight
-    gemm_epilogue<TM, TN, OUT_BF16, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
                                             it.n0 + wn * WN, it.batch, it.z);
     zero_acc();
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16>
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC>
 static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = 2 * (BM + BN) * ROWB;
-  auto kfn = gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC, OUT_BF16>;
+  auto kfn = gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC, OUT_BF16, VEC>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -727,10 +830,10 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool AKC, bool BKC, bool OUT_BF16>
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC>
 static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = PP_SMEM;
-  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16>;
+  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16, VEC>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -745,26 +848,28 @@ static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
   return hipGetLastError();
 }
 
-static hipError_t launch_big(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
+// operand orientations x output type x epilogue form -> kernel instance
+template <bool BIG, bool AKC, bool BKC>
+static hipError_t launch_oriented(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
   const bool obf = g.c_bf16 && g.splits <= 1;
-  if (g.a_kc && g.b_kc) return obf ? launch_pp<true, true, true>(d, g.batch, st) : launch_pp<true, true, false>(d, g.batch, st);
-  if (g.a_kc && !g.b_kc) return obf ? launch_pp<true, false, true>(d, g.batch, st) : launch_pp<true, false, false>(d, g.batch, st);
-  if (!g.a_kc && !g.b_kc) return obf ? launch_pp<false, false, true>(d, g.batch, st) : launch_pp<false, false, false>(d, g.batch, st);
-  return hipErrorInvalidValue;
+  const bool vec = d.vec_ok != 0;
+  if constexpr (BIG) {
+    if (obf) return vec ? launch_pp<AKC, BKC, true, true>(d, g.batch, st) : launch_pp<AKC, BKC, true, false>(d, g.batch, st);
+    return vec ? launch_pp<AKC, BKC, false, true>(d, g.batch, st) : launch_pp<AKC, BKC, false, false>(d, g.batch, st);
+  } else {
+    if (obf)
+      return vec ? launch_one<128, 128, 2, 2, AKC, BKC, true, true>(d, g.batch, st)
+                 : launch_one<128, 128, 2, 2, AKC, BKC, true, false>(d, g.batch, st);
+    return vec ? launch_one<128, 128, 2, 2, AKC, BKC, false, true>(d, g.batch, st)
+               : launch_one<128, 128, 2, 2, AKC, BKC, false, false>(d, g.batch, st);
+  }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <bool BIG>
 static hipError_t launch_tile(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
-  const bool obf = g.c_bf16 && g.splits <= 1;
-  if (g.a_kc && g.b_kc)
-    return obf ? launch_one<BM, BN, WGM, WGN, true, true, true>(d, g.batch, st)
-               : launch_one<BM, BN, WGM, WGN, true, true, false>(d, g.batch, st);
-  if (g.a_kc && !g.b_kc)
-    return obf ? launch_one<BM, BN, WGM, WGN, true, false, true>(d, g.batch, st)
-               : launch_one<BM, BN, WGM, WGN, true, false, false>(d, g.batch, st);
-  if (!g.a_kc && !g.b_kc)
-    return obf ? launch_one<BM, BN, WGM, WGN, false, false, true>(d, g.batch, st)
-               : launch_one<BM, BN, WGM, WGN, false, false, false>(d, g.batch, st);
+  if (g.a_kc && g.b_kc) return launch_oriented<BIG, true, true>(g, d, st);
+  if (g.a_kc && !g.b_kc) return launch_oriented<BIG, true, false>(g, d, st);
+  if (!g.a_kc && !g.b_kc) return launch_oriented<BIG, false, false>(g, d, st);
   return hipErrorInvalidValue;  // (A strided, B contiguous) is not used by the path
 }
 
@@ -809,14 +914,16 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   // vector epilogue: every row of C / C_lo / C_dact / gate starts 16-byte aligned
   // (ldc % 4 == 0 gives 8-byte alignment for bf16 rows, which their 8-byte stores need)
   d.vec_ok = ((g.ldc & 3) == 0) && ((g.sC & 3) == 0) && al16(g.C) && (!g.C_lo || al16(g.C_lo)) &&
-             (!g.C_dact || al16(g.C_dact)) && (!g.gate || (al16(g.gate) && (g.ldg & 3) == 0));
+             (!g.C_dact || al16(g.C_dact)) && (!g.gate || (al16(g.gate) && (g.ldg & 3) == 0)) &&
+             (g.N & 3) == 0 &&                                            // a 4-column group is all in or all out
+             g.ldc < (1 << 21) && g.ldg < (1 << 21) && g.N < (1 << 21);   // 32-bit byte offsets inside a 128-row window
   const int bm = big_tile ? 256 : 128;
   d.tiles_m = (g.M + bm - 1) / bm;
   d.tiles_n = (g.N + bm - 1) / bm;
   const int ktiles = (g.K[0] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
-  return big_tile ? launch_big(g, d, st) : launch_tile<128, 128, 2, 2>(g, d, st);
+  return big_tile ? launch_tile<true>(g, d, st) : launch_tile<false>(g, d, st);
 }
 
 }  // namespace asx
