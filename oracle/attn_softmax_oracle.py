@@ -39,8 +39,11 @@ def _as64(x):
     return np.asarray(x, dtype=F64)
 
 
-def _sentence_forward(Hd, Se_full, L, W_a, W_c, W_out, b_out, y, pad_id):
-    """Forward for one sentence.  Hd [T,H], Se_full [S,H], L valid source positions."""
+def _sentence_forward(Hd, Se_full, L, W_a, W_c, W_out, b_out, y, pad_id, Dm=None):
+    """Forward for one sentence.  Hd [T,H], Se_full [S,H], L valid source positions.
+
+    Dm [T,H] (optional): dropout multiplier on h~ (0 or 1/(1-p)); the output
+    projection then sees Hu = Dm * h~ while tanh' in the backward pass keeps h~."""
     T, H = Hd.shape
     S = Se_full.shape[0]
     V = W_out.shape[0]
@@ -55,25 +58,27 @@ def _sentence_forward(Hd, Se_full, L, W_a, W_c, W_out, b_out, y, pad_id):
     C = alpha[:, :L] @ Se                         # Eq. 3
     Z = C @ W_c[:, :H].T + Hd @ W_c[:, H:].T      # W_c [c ; h_t]
     Ht = np.tanh(Z)                               # Eq. 4
-    logits = Ht @ W_out.T + b_out                 # Eq. 5, F_c
+    Hu = Ht if Dm is None else Ht * Dm            # what the output layer is fed
+    logits = Hu @ W_out.T + b_out                 # Eq. 5, F_c
     M = logits.max(axis=1)
     lse = M + np.log(np.exp(logits - M[:, None]).sum(axis=1))
     nonpad = (y != pad_id) & (y >= 0) & (y < V)
     ysafe = np.where(nonpad, y, 0)
     tok_loss = np.where(nonpad, lse - logits[np.arange(T), ysafe], 0.0)   # -log P_i, Eq. 6
     argmax = logits.argmax(axis=1)                # numpy returns the first (lowest) maximiser
-    return dict(Q=Q, alpha=alpha, C=C, Ht=Ht, logits=logits, lse=lse,
+    return dict(Q=Q, alpha=alpha, C=C, Ht=Ht, Hu=Hu, logits=logits, lse=lse,
                 nonpad=nonpad, ysafe=ysafe, tok_loss=tok_loss, argmax=argmax)
 
 
 def forward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
-            keep_logits=True, sentences=None):
+            keep_logits=True, sentences=None, drop=None):
     """Forward pass for the whole batch (or the listed sentences).
 
     h_dec [T,B,H], h_enc [S,B,H], src_len [B], W_a [H,H], W_c [H,2H],
     W_out [V,H], b_out [V], targets [T,B].  Returns a dict; per-sentence arrays
     keep the caller's layout ([T,B,...], alpha as [B,T,S]) and hold zeros for
-    sentences that were not requested.
+    sentences that were not requested.  drop [T,B,H] (optional) is the dropout
+    multiplier on h~; the returned h_c is then the dropped, rescaled h~.
     """
     h_dec, h_enc = _as64(h_dec), _as64(h_enc)
     W_a, W_c, W_out, b_out = _as64(W_a), _as64(W_c), _as64(W_out), _as64(b_out)
@@ -94,10 +99,10 @@ def forward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
     for b in todo:
         L = int(min(max(int(src_len[b]), 0), S))
         r = _sentence_forward(h_dec[:, b], h_enc[:, b], L, W_a, W_c, W_out, b_out,
-                              targets[:, b], pad_id)
+                              targets[:, b], pad_id, None if drop is None else drop[:, b])
         out["alpha"][b] = r["alpha"]
         out["ctx"][:, b] = r["C"]
-        out["h_c"][:, b] = r["Ht"]
+        out["h_c"][:, b] = r["Hu"]
         out["lse"][:, b] = r["lse"]
         out["tok_loss"][:, b] = r["tok_loss"]
         out["argmax"][:, b] = r["argmax"]
@@ -113,7 +118,7 @@ def forward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
 
 
 def backward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
-             grad_scale=1.0, keep_dlogits=False, sentences=None):
+             grad_scale=1.0, keep_dlogits=False, sentences=None, drop=None):
     """Gradients of  grad_scale * loss_sum  (loss_sum over the listed sentences).
 
     Returns d_h_dec [T,B,H], d_h_enc [S,B,H], dW_a, dW_c, dW_out, db_out (and
@@ -139,7 +144,8 @@ def backward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
         L = int(min(max(int(src_len[b]), 0), S))
         Hd = h_dec[:, b]
         Se = h_enc[:L, b]
-        r = _sentence_forward(Hd, h_enc[:, b], L, W_a, W_c, W_out, b_out, targets[:, b], pad_id)
+        Dm = None if drop is None else drop[:, b]
+        r = _sentence_forward(Hd, h_enc[:, b], L, W_a, W_c, W_out, b_out, targets[:, b], pad_id, Dm)
         # d loss / d logits = softmax - onehot on non-pad rows, 0 on pad rows
         P = np.exp(r["logits"] - r["lse"][:, None])
         dlog = P
@@ -148,8 +154,10 @@ def backward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
         if keep_dlogits:
             dlogits_all[:, b] = dlog
         db_out += dlog.sum(axis=0)
-        dW_out += dlog.T @ r["Ht"]
-        dHt = dlog @ W_out
+        dW_out += dlog.T @ r["Hu"]
+        dHt = dlog @ W_out                                   # gradient at the output layer's input
+        if Dm is not None:
+            dHt = dHt * Dm                                   # back through the dropout multiplier
         dZ = dHt * (1.0 - r["Ht"] ** 2)                      # tanh'
         dW_c[:, :H] += dZ.T @ r["C"]
         dW_c[:, H:] += dZ.T @ Hd
@@ -169,7 +177,7 @@ def backward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id,
     return out
 
 
-def scaled_loss(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id, grad_scale=1.0):
+def scaled_loss(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id, grad_scale=1.0, drop=None):
     """The scalar whose gradient `backward` returns."""
-    f = forward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id, keep_logits=False)
+    f = forward(h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, pad_id, keep_logits=False, drop=drop)
     return grad_scale * f["loss_sum"]
