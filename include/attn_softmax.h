@@ -67,6 +67,16 @@ typedef struct {
   int32_t pad_id;          /* 0 <= pad_id < V */
   int32_t dtype;           /* as_dtype */
   float grad_scale;        /* g: gradients are those of g * loss_sum */
+  /* Dropout on h_c (section 4.2, "Parameter settings": a dropout of 0.3), applied
+   * after Eq. 4 and before Eq. 5 as inverted dropout: element (t,b,c), flat index
+   * i = (t*B + b)*H + c, is kept iff word (i & 3) of philox4x32-10(counter = i >> 2,
+   * key = dropout_seed) is >= floor(dropout_p * 2^32); kept elements are multiplied
+   * by 1/(1 - dropout_p), dropped ones are 0.  AS_VIEW_HC then holds the dropped,
+   * rescaled h_c, and the backward pass goes through the same mask (it is saved in
+   * the workspace with the tanh derivative, not drawn again).  0 <= dropout_p < 1;
+   * 0 switches it off.  The caller changes dropout_seed from step to step. */
+  float dropout_p;
+  uint64_t dropout_seed;
 } as_shape;
 
 /* Saved activations readable through attn_softmax_view(). */
@@ -160,12 +170,38 @@ typedef enum {
   AS_STAGE_GEMM_DWA = 14,     /* dW_a = h_dec^T dQ                           */
   AS_STAGE_GEMM_DH = 15,      /* d_h_dec = dH1 + dQ W_a^T                    */
   AS_STAGE_MISC = 16,         /* small reductions, split-K combine           */
-  AS_STAGE_COUNT = 17
+  AS_STAGE_ADAM = 17,         /* attn_softmax_adam_step                      */
+  AS_STAGE_COUNT = 18
 } as_stage;
 
 as_status attn_softmax_profile_enable(int enable);
 /* ms_total[AS_STAGE_COUNT], launches[AS_STAGE_COUNT]; either may be NULL. */
 as_status attn_softmax_profile_read(double* ms_total, int64_t* launches);
+
+/*
+ * One Adam update of one parameter tensor of this part of the model (section
+ * 4.2, "Parameter settings": Adam with beta1 = 0.9, beta2 = 0.999, eps = 1e-8;
+ * Table 2: initial learning rate 0.001), bias-corrected as in Kingma and Ba's
+ * Algorithm 1:
+ *   m = beta1 m + (1 - beta1) g ;  v = beta2 v + (1 - beta2) g^2
+ *   master -= lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * n elements; grad [n] float (as attn_softmax_bwd wrote it, read only);
+ * master, m, v [n] float, updated in place (m = v = 0 before step 1);
+ * weights_out [n] of `dtype` (optional): the updated master rounded to the
+ * storage type the forward pass reads (round to nearest even for AS_BF16).
+ * All pointers are device memory, 16-byte aligned; step >= 1; the learning-rate
+ * decay of the paper is the caller's policy (pass the decayed lr).
+ * Errors: AS_ERR_NULL, AS_ERR_SHAPE (n = 0, step < 1, betas outside [0,1)),
+ * AS_ERR_DTYPE, AS_ERR_ALIGN, AS_ERR_HIP.
+ */
+typedef struct {
+  float lr, beta1, beta2, eps;
+  int32_t step;            /* 1 for the first update */
+} as_adam;
+
+as_status attn_softmax_adam_step(const as_adam* hyper, size_t n, const float* grad,
+                                 float* master, float* m, float* v,
+                                 void* weights_out, int32_t dtype, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -3,6 +3,7 @@ data-model parallel Seq2Seq RNN MT paper) as a C-ABI HIP library plus this thin
 ctypes binding.  Importing the package does not load the library; the first
 call does, and fails loudly if it has not been built."""
 from .binding import (  # noqa: F401
-    AS_BF16, AS_F32, STAGE_NAMES, AsShape, AttnSoftmaxError, DeviceBatch, attn_softmax_bwd,
+    AS_BF16, AS_F32, STAGE_NAMES, AsAdam, AsShape, AttnSoftmaxError, DeviceBatch, attn_softmax_adam_step,
+    attn_softmax_bwd,
     attn_softmax_fwd, attn_softmax_last_error, attn_softmax_profile_enable,
     attn_softmax_profile_read, attn_softmax_view, attn_softmax_workspace_bytes, library_path, load_library)

@@ -22,9 +22,10 @@ STATUS_NAMES = {0: "AS_OK", 1: "AS_ERR_NULL", 2: "AS_ERR_SHAPE", 3: "AS_ERR_DTYP
                 4: "AS_ERR_WORKSPACE", 5: "AS_ERR_ALIGN", 6: "AS_ERR_HIP"}
 STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "gemm_logits",
                "xent_stats", "xent_dlogits", "gemm_dwout", "gemm_dhc", "gemm_dwc", "gemm_dch",
-               "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc"]
+               "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam"]
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
-           "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read"]
+           "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
+           "attn_softmax_adam_step"]
 
 
 class AttnSoftmaxError(RuntimeError):
@@ -36,7 +37,13 @@ class AttnSoftmaxError(RuntimeError):
 class AsShape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("S", ctypes.c_int32), ("B", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("pad_id", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("grad_scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("grad_scale", ctypes.c_float),
+                ("dropout_p", ctypes.c_float), ("dropout_seed", ctypes.c_uint64)]
+
+
+class AsAdam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("step", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -68,6 +75,8 @@ def load_library():
     lib.attn_softmax_profile_enable.argtypes = [ctypes.c_int]
     lib.attn_softmax_profile_read.restype = ctypes.c_int
     lib.attn_softmax_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.attn_softmax_adam_step.restype = ctypes.c_int
+    lib.attn_softmax_adam_step.argtypes = [ctypes.POINTER(AsAdam), sz, vp, vp, vp, vp, vp, ctypes.c_int32, vp]
     _lib = lib
     return lib
 
@@ -126,6 +135,15 @@ def attn_softmax_view(shape, workspace, which: int):
     return int(p.value), int(n.value), int(ld.value)
 
 
+def attn_softmax_adam_step(hyper: AsAdam, n: int, grad, master, m, v, weights_out, dtype: int, stream: int = 0,
+                           check=True) -> int:
+    rc = load_library().attn_softmax_adam_step(ctypes.byref(hyper) if hyper is not None else None, n, _ptr(grad),
+                                               _ptr(master), _ptr(m), _ptr(v), _ptr(weights_out), dtype, stream)
+    if check:
+        _check(rc)
+    return rc
+
+
 def attn_softmax_profile_enable(enable: bool):
     _check(load_library().attn_softmax_profile_enable(1 if enable else 0))
 
@@ -149,7 +167,8 @@ class DeviceBatch:
         self.dev = torch.device(device)
         bf = inp.dtype == "bf16"
         self.shape = AsShape(inp.T, inp.S, inp.B, inp.H, inp.V, inp.pad_id, AS_BF16 if bf else AS_F32,
-                             float(inp.grad_scale))
+                             float(inp.grad_scale), float(getattr(inp, "dropout_p", 0.0)),
+                             int(getattr(inp, "dropout_seed", 0)))
         tdt = torch.bfloat16 if bf else torch.float32
         self.tdt = tdt
 

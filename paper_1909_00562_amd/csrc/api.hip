@@ -4,6 +4,7 @@
 #include "../../include/attn_softmax.h"
 
 #include <hip/hip_runtime.h>
+#include <cmath>
 
 #include <cstdarg>
 #include <cstdio>
@@ -90,6 +91,7 @@ bool shape_ok(const as_shape* s) {
   if (!s) return false;
   if (s->T < 1 || s->S < 1 || s->B < 1 || s->H < 1 || s->V < 1) return false;
   if (s->pad_id < 0 || s->pad_id >= s->V) return false;
+  if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return false;
   if (s->dtype != AS_F32 && s->dtype != AS_BF16) return false;
   const int64_t N = (int64_t)s->T * s->B;
   if (N > (1 << 30) || (int64_t)s->S * s->B > (1 << 30)) return false;
@@ -174,8 +176,8 @@ as_status check_common(const as_shape* s, const void* h_dec, const void* h_enc, 
   if (!s) return fail(AS_ERR_NULL, "shape is NULL");
   if (s->dtype != AS_F32 && s->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", s->dtype);
   if (!shape_ok(s))
-    return fail(AS_ERR_SHAPE, "bad shape T=%d S=%d B=%d H=%d V=%d pad_id=%d", s->T, s->S, s->B, s->H, s->V,
-                s->pad_id);
+    return fail(AS_ERR_SHAPE, "bad shape T=%d S=%d B=%d H=%d V=%d pad_id=%d dropout_p=%g", s->T, s->S, s->B, s->H,
+                s->V, s->pad_id, (double)s->dropout_p);
   if (!h_dec || !h_enc || !src_len || !W_a || !W_c || !W_out || !b_out || !targets || !ws)
     return fail(AS_ERR_NULL, "a required pointer is NULL");
   if (s->dtype == AS_BF16 && (s->H % 8) != 0) return fail(AS_ERR_ALIGN, "AS_BF16 needs H %% 8 == 0 (H=%d)", s->H);
@@ -292,6 +294,11 @@ as_status attn_softmax_fwd(const as_shape* s, const void* h_dec, const void* h_e
     g.M = N; g.N = H; g.act_tanh = 1;
     g.C = w + L.hc; g.ldc = H; g.c_bf16 = bf;
     g.C_dact = reinterpret_cast<float*>(w + L.dact);
+    if (s->dropout_p > 0.f) {   // section 4.2: dropout, here on the attentional state; the mask rides on dact into bwd
+      g.drop_thr = (uint32_t)((double)s->dropout_p * 4294967296.0);   // floor: the product is exact in double
+      g.drop_scale = 1.f / (1.f - s->dropout_p);
+      g.drop_seed = s->dropout_seed;
+    }
     AS_TRY(AS_STAGE_GEMM_HC, launch_gemm(g, bf, L.p_hc.big_tile, st));
   }
   {  // logits = h_c W_out^T + b_out                                        (Eq. 5)
@@ -441,6 +448,25 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
     g.C = d_h_dec; g.ldc = H; g.c_bf16 = false; g.accumulate = 1;
     AS_TRY(AS_STAGE_GEMM_DH, launch_gemm(g, bf, L.p_dh.big_tile, st));
   }
+  return AS_OK;
+}
+
+as_status attn_softmax_adam_step(const as_adam* hp, size_t n, const float* grad, float* master, float* m, float* v,
+                                 void* weights_out, int32_t dtype, void* hip_stream) {
+  if (!hp || !grad || !master || !m || !v) return fail(AS_ERR_NULL, "a required pointer is NULL");
+  if (n == 0 || hp->step < 1 || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f))
+    return fail(AS_ERR_SHAPE, "bad Adam arguments n=%zu step=%d beta1=%g beta2=%g", n, hp->step, (double)hp->beta1,
+                (double)hp->beta2);
+  if (weights_out && dtype != AS_F32 && dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", dtype);
+  const void* ptrs[] = {grad, master, m, v, weights_out};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return fail(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  // bias corrections in double on the host: 1 - beta^step loses nothing for small steps that way
+  const float inv_bc1 = (float)(1.0 / (1.0 - std::pow((double)hp->beta1, (double)hp->step)));
+  const float inv_bc2 = (float)(1.0 / (1.0 - std::pow((double)hp->beta2, (double)hp->step)));
+  AS_TRY(AS_STAGE_ADAM, launch_adam_step(n, grad, master, m, v, weights_out, dtype == AS_BF16, hp->lr, hp->beta1,
+                                         hp->beta2, hp->eps, inv_bc1, inv_bc2, st));
   return AS_OK;
 }
 

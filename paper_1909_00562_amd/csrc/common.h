@@ -46,6 +46,37 @@ template <> __device__ __forceinline__ float round_elem<uint16_t>(float v) {
   return bf16_bits_to_f32(f32_to_bf16_bits(v));
 }
 
+// philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0..c3), key (k0,k1) -> w[4]
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&w)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) {
+      k0 += 0x9E3779B9u;
+      k1 += 0xBB67AE85u;
+    }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0;
+    c1 = lo1;
+    c2 = hi0 ^ c3 ^ k1;
+    c3 = lo0;
+  }
+  w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+}
+// the four random words of the elements with flat indices 4q .. 4q+3
+__device__ __forceinline__ void dropout_words4(uint64_t q, uint64_t seed, uint32_t (&w)[4]) {
+  philox4x32_10((uint32_t)q, (uint32_t)(q >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w);
+}
+// multiplier of the element with flat index i: scale if kept, 0 if dropped
+__device__ __forceinline__ float dropout_mult(uint64_t i, uint64_t seed, uint32_t thr, float scale) {
+  uint32_t w[4];
+  dropout_words4(i >> 2, seed, w);
+  const uint32_t k = (uint32_t)i & 3u;
+  const uint32_t word = k == 0 ? w[0] : k == 1 ? w[1] : k == 2 ? w[2] : w[3];
+  return word >= thr ? scale : 0.f;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

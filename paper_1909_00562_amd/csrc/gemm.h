@@ -20,6 +20,10 @@
 // C[m,n] = v rounded to the output type.  Optional second outputs with C's
 // layout:  C_lo[m,n] = v - C[m,n] (type of C), the part of v the rounding lost;
 // C_dact[m,n] = 1 - v^2 as float (the tanh derivative, taken before v is rounded).
+// Dropout (drop_thr != 0, after the activation): element (m,n) draws the 32-bit word
+// philox4x32-10(counter = (m*N + n) >> 2, key = drop_seed)[(m*N + n) & 3]; it is kept iff
+// word >= drop_thr.  Kept: v and C_dact are multiplied by drop_scale; dropped: both are 0,
+// so that a later product with C_dact as its gate also backpropagates through the mask.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -52,6 +56,9 @@ struct GemmArgs {
   int64_t ldg = 0;
   int act_tanh = 0;
   int accumulate = 0;
+  uint32_t drop_thr = 0;        // 0 = no dropout
+  float drop_scale = 1.f;       // 1 / (1 - p)
+  uint64_t drop_seed = 0;
   int batch = 1;
   int splits = 1;               // split of the reduction index (single segment only)
   float* partial = nullptr;     // [batch*splits, M, N] floats when splits > 1

@@ -42,6 +42,9 @@ struct GemmDev {
   const float* gate;
   int64_t ldg;
   int act_tanh, accumulate;
+  uint32_t drop_thr;
+  float drop_scale;
+  uint64_t drop_seed;
   int splits;
   float* partial;
   int tiles_m, tiles_n;
@@ -203,6 +206,17 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
 #pragma unroll
         for (int c = 0; c < 4; ++c) v[c] = tanhf(v[c]);
       }
+      float dact[4] = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
+      if (fuse && p.drop_thr) {   // the lane's four columns are one block of the generator (N % 4 == 0)
+        uint32_t w[4];
+        dropout_words4(((uint64_t)(row0 + vrow + nrow) * p.N + (uint32_t)(col0 + vcol)) >> 2, p.drop_seed, w);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float sc = w[c] >= p.drop_thr ? p.drop_scale : 0.f;
+          v[c] *= sc;
+          dact[c] *= sc;
+        }
+      }
       if (fuse && p.gate && in) {
         const f32x4_t g4 = *reinterpret_cast<const f32x4_t*>(gate0 + (uint32_t)nrow * ldg32 + lane_off_g);
 #pragma unroll
@@ -221,8 +235,8 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
           __builtin_amdgcn_raw_buffer_store_b64(lv, rs_lo, off, row_el * 2u, 0);
         }
         if (p.C_dact) {
-          const u32x4_t dv = {__builtin_bit_cast(uint32_t, 1.f - v[0] * v[0]), __builtin_bit_cast(uint32_t, 1.f - v[1] * v[1]),
-                              __builtin_bit_cast(uint32_t, 1.f - v[2] * v[2]), __builtin_bit_cast(uint32_t, 1.f - v[3] * v[3])};
+          const u32x4_t dv = {__builtin_bit_cast(uint32_t, dact[0]), __builtin_bit_cast(uint32_t, dact[1]),
+                              __builtin_bit_cast(uint32_t, dact[2]), __builtin_bit_cast(uint32_t, dact[3])};
           __builtin_amdgcn_raw_buffer_store_b128(dv, rs_da, in ? lane_off * 4u : kOob, row_el * 4u, 0);
         }
       } else {
@@ -308,10 +322,17 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
             if (gcol + c < p.N) gt[c] = gp[c];
         }
       }
+      float dact[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         float x = v[c] + bias4[c];
         if (p.act_tanh) x = tanhf(x);
+        dact[c] = 1.f - x * x;
+        if (p.drop_thr && gcol + c < p.N) {
+          const float sc = dropout_mult((uint64_t)grow * p.N + (gcol + c), p.drop_seed, p.drop_thr, p.drop_scale);
+          x *= sc;
+          dact[c] *= sc;
+        }
         v[c] = x * gt[c];
       }
       if constexpr (OUT_BF16) {
@@ -328,7 +349,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
           if (p.C_lo)
             *reinterpret_cast<uint2*>(p.C_lo + ci) = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
           if (p.C_dact) {
-            f32x4_t d4 = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
+            f32x4_t d4 = {dact[0], dact[1], dact[2], dact[3]};
             *reinterpret_cast<f32x4_t*>(p.C_dact + ci) = d4;
           }
         } else {
@@ -337,7 +358,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
             if (gcol + c < p.N) {
               C[c] = (uint16_t)hb[c];
               if (p.C_lo) p.C_lo[ci + c] = (uint16_t)f32_to_bf16_bits(lo[c]);
-              if (p.C_dact) p.C_dact[ci + c] = 1.f - v[c] * v[c];
+              if (p.C_dact) p.C_dact[ci + c] = dact[c];
             }
         }
       } else {
@@ -877,7 +898,8 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   if (g.M < 1 || g.N < 1 || g.batch < 1 || g.splits < 1) return hipErrorInvalidValue;
-  if (g.splits > 1 && (g.K[1] != 0 || g.partial == nullptr || g.C_dact)) return hipErrorInvalidValue;
+  if (g.splits > 1 && (g.K[1] != 0 || g.partial == nullptr || g.C_dact || g.drop_thr)) return hipErrorInvalidValue;
+  if (g.drop_thr && g.batch != 1) return hipErrorInvalidValue;   // flat element index = m * N + n
   if ((g.C_lo || g.C_dact) && !g.c_bf16) return hipErrorInvalidValue;
   GemmDev d;
   for (int s = 0; s < kMaxSeg; ++s) {
@@ -908,6 +930,9 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   d.gate = g.gate;
   d.ldg = g.ldg;
   d.act_tanh = g.act_tanh;
+  d.drop_thr = g.drop_thr;
+  d.drop_scale = g.drop_scale;
+  d.drop_seed = g.drop_seed;
   d.accumulate = g.accumulate;
   d.splits = g.splits;
   d.partial = g.partial;

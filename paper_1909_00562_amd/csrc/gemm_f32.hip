@@ -21,6 +21,9 @@ struct GemmDevF {
   const float* gate;
   int64_t ldg;
   int act_tanh, accumulate;
+  uint32_t drop_thr;
+  float drop_scale;
+  uint64_t drop_seed;
   int splits;
   float* partial;
   int kper;
@@ -100,13 +103,19 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
       }
       if (p.bias) v += (double)p.bias[col];
       if (p.act_tanh) v = tanh(v);
+      double dact = 1.0 - v * v;
+      if (p.drop_thr) {
+        const double s = (double)dropout_mult((uint64_t)row * p.N + col, p.drop_seed, p.drop_thr, p.drop_scale);
+        v *= s;
+        dact *= s;
+      }
       if (p.gate) v *= (double)p.gate[(int64_t)row * p.ldg + col];
       const int64_t ci = (int64_t)batch * p.sC + (int64_t)row * p.ldc + col;
       if (p.accumulate) v += (double)p.C[ci];
       const float vf = (float)v;
       p.C[ci] = vf;
       if (p.C_lo) p.C_lo[ci] = (float)(v - (double)vf);
-      if (p.C_dact) p.C_dact[ci] = (float)(1.0 - v * v);
+      if (p.C_dact) p.C_dact[ci] = (float)dact;
     }
   }
 }
@@ -114,7 +123,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st) {
   if (g.M < 1 || g.N < 1 || g.batch < 1 || g.splits < 1 || g.c_bf16) return hipErrorInvalidValue;
   if (g.splits > 1 && (g.K[1] != 0 || g.partial == nullptr)) return hipErrorInvalidValue;
-  if (g.splits > 1 && g.C_dact) return hipErrorInvalidValue;
+  if (g.splits > 1 && (g.C_dact || g.drop_thr)) return hipErrorInvalidValue;
+  if (g.drop_thr && g.batch != 1) return hipErrorInvalidValue;
   GemmDevF d;
   for (int s = 0; s < kMaxSeg; ++s) {
     d.A[s] = reinterpret_cast<const float*>(g.A[s]);
@@ -138,6 +148,9 @@ hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st) {
   d.gate = g.gate;
   d.ldg = g.ldg;
   d.act_tanh = g.act_tanh;
+  d.drop_thr = g.drop_thr;
+  d.drop_scale = g.drop_scale;
+  d.drop_seed = g.drop_seed;
   d.accumulate = g.accumulate;
   d.splits = g.splits;
   d.partial = g.partial;

@@ -2,6 +2,7 @@
 // softmax cross-entropy).  All enqueue on `st` and return the launch status.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 namespace asx {
@@ -35,5 +36,10 @@ hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, in
                                int pad_id, const float* lse, float g, float* db_partial, hipStream_t st);
 // db_out[v] = sum_rb db_partial[rb][v]
 hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st);
+
+// Adam, bias corrections passed as inv_bc1 = 1 / (1 - beta1^step), inv_bc2 likewise; wout optional.
+hipError_t launch_adam_step(size_t n, const float* grad, float* master, float* m, float* v, void* wout,
+                            bool out_bf16, float lr, float beta1, float beta2, float eps, float inv_bc1,
+                            float inv_bc2, hipStream_t st);
 
 }  // namespace asx

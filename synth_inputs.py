@@ -80,6 +80,8 @@ class Inputs:
     b_out: np.ndarray     # [V]
     targets: np.ndarray   # [T,B] int32
     grad_scale: float = 1.0
+    dropout_p: float = 0.0   # rate of the dropout on the attentional state (0 = off) and its seed
+    dropout_seed: int = 0
     extra: dict = field(default_factory=dict)
 
     FLOAT_FIELDS = ("h_dec", "h_enc", "W_a", "W_c", "W_out", "b_out")

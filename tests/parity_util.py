@@ -27,10 +27,19 @@ def oracle_args(inp):
             inp.targets, inp.pad_id)
 
 
+def oracle_drop(inp):
+    """Dropout multiplier of the batch (None when dropout is off)."""
+    if getattr(inp, "dropout_p", 0.0) <= 0.0:
+        return None
+    from oracle import train_extras_oracle as tx
+    return tx.dropout_multiplier(inp.T, inp.B, inp.H, inp.dropout_p, inp.dropout_seed)
+
+
 def run_oracle(inp, keep_logits=True, keep_dlogits=False, sentences=None):
-    f = orc.forward(*oracle_args(inp), keep_logits=keep_logits, sentences=sentences)
+    drop = oracle_drop(inp)
+    f = orc.forward(*oracle_args(inp), keep_logits=keep_logits, sentences=sentences, drop=drop)
     g = orc.backward(*oracle_args(inp), grad_scale=inp.grad_scale, keep_dlogits=keep_dlogits,
-                     sentences=sentences)
+                     sentences=sentences, drop=drop)
     return f, g
 
 

@@ -112,3 +112,28 @@ def test_profile_calls_work_without_a_device():
     bd.attn_softmax_profile_enable(False)
     r = bd.attn_softmax_profile_read()
     assert set(r) == set(bd.STAGE_NAMES) and all(v["launches"] == 0 for v in r.values())
+
+
+def test_dropout_rate_is_validated():
+    s = _shape()
+    s.dropout_p = 0.3
+    s.dropout_seed = 2 ** 63 + 5
+    assert bd.attn_softmax_workspace_bytes(s) == bd.attn_softmax_workspace_bytes(_shape())
+    for bad in (1.0, -0.1, float("nan")):
+        s.dropout_p = bad
+        assert bd.attn_softmax_workspace_bytes(s) == 0
+        assert _call_fwd(s) == 2
+
+
+def test_adam_rejects_bad_arguments_before_any_launch():
+    ok = bd.AsAdam(1e-3, 0.9, 0.999, 1e-8, 1)
+    call = lambda hp, n=64, grad=0x1000, master=0x2000, m=0x3000, v=0x4000, out=None, dtype=bd.AS_F32: \
+        bd.attn_softmax_adam_step(hp, n, grad, master, m, v, out, dtype, 0, check=False)
+    assert call(None) == 1
+    assert call(ok, grad=None) == 1 and call(ok, v=None) == 1
+    assert call(ok, n=0) == 2
+    assert call(bd.AsAdam(1e-3, 0.9, 0.999, 1e-8, 0)) == 2
+    assert call(bd.AsAdam(1e-3, 1.0, 0.999, 1e-8, 1)) == 2
+    assert call(bd.AsAdam(1e-3, 0.9, -0.5, 1e-8, 1)) == 2
+    assert call(ok, out=0x5000, dtype=9) == 3
+    assert call(ok, m=0x3004) == 5
