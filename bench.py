@@ -18,6 +18,11 @@ roofline_hbm = the two streaming softmax-cross-entropy kernels against the 8 TB/
              the in-place dlogits pass)
 cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
              sentences of the same workload (a reported baseline, not a target)
+adam       = the fused Adam update of the four parameter tensors (outside the timed
+             steps unless --train-step): 30 bytes per element (bf16 storage copy)
+             or 32 (f32) against the HBM peak
+--train-step makes a step = forward with dropout 0.3 + backward + Adam on the four
+             parameter tensors (the headline metric stays forward + backward)
 """
 from __future__ import annotations
 
@@ -92,6 +97,8 @@ def main():
     ap.add_argument("--workload", default="stress", choices=["tiny", "small", "mid", "large", "stress"])
     ap.add_argument("--dtype", default=None, choices=["bf16", "f32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--train-step", action="store_true",
+                    help="a step = fwd with dropout 0.3 + bwd + Adam update of W_a, W_c, W_out, b_out")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -121,15 +128,38 @@ def main():
         return
 
     inp = make_inputs(a.workload, dtype=a.dtype)
+    if a.train_step:
+        inp.dropout_p, inp.dropout_seed = 0.3, 20190900562
     db = lib.DeviceBatch(inp)
     T, S, B, H, V = inp.T, inp.S, inp.B, inp.H, inp.V
     N = T * B
     e = 2 if inp.dtype == "bf16" else 4
     n_tok = inp.n_nonpad()
 
+    # Adam state of the four parameter tensors: float master copy and both moments
+    params = [("W_a", "dW_a"), ("W_c", "dW_c"), ("W_out", "dW_out"), ("b_out", "db_out")]
+    adam_state = {p: (getattr(db, p).float().contiguous(), torch.zeros_like(getattr(db, p), dtype=torch.float32),
+                      torch.zeros_like(getattr(db, p), dtype=torch.float32)) for p, _ in params}
+    n_params = sum(getattr(db, p).numel() for p, _ in params)
+    store = lib.AS_BF16 if inp.dtype == "bf16" else lib.AS_F32
+    adam_t = [0]
+
+    def adam():
+        adam_t[0] += 1
+        hp = lib.AsAdam(1e-3, 0.9, 0.999, 1e-8, adam_t[0])
+        st = int(torch.cuda.current_stream().cuda_stream)
+        for p, gname in params:
+            master, m1, m2 = adam_state[p]
+            lib.attn_softmax_adam_step(hp, master.numel(), getattr(db, gname), master, m1, m2, getattr(db, p),
+                                       store, st)
+
     def step():
+        if a.train_step:
+            db.shape.dropout_seed += 1
         db.fwd()
         db.bwd()
+        if a.train_step:
+            adam()
 
     for _ in range(a.warmup):
         step()
@@ -144,6 +174,17 @@ def main():
     stages = lib.attn_softmax_profile_read()
     lib.attn_softmax_profile_enable(False)
     assert int(db.n_tok.item()) == n_tok
+
+    # the Adam update on its own (gradients of the last step), HIP events on the launch stream
+    adam(); db.sync()
+    lib.attn_softmax_profile_enable(True)
+    n_adam = 5
+    for _ in range(n_adam):
+        adam()
+    db.sync()
+    adam_ms = lib.attn_softmax_profile_read()["adam"]["ms"] / n_adam
+    lib.attn_softmax_profile_enable(False)
+    adam_bytes = n_params * (30.0 if inp.dtype == "bf16" else 32.0)
 
     ms_step = dt / a.steps * 1e3
     per_stage = {k: (v["ms"] / v["launches"] if v["launches"] else 0.0) for k, v in stages.items()}
@@ -193,6 +234,11 @@ def main():
         "roofline": roofline,
         "roofline_hbm": roofline_hbm,
         "stage_ms_per_step": {k: round(v, 5) for k, v in step_ms_by_stage.items()},
+        "adam": {"kernel": "adam_step (W_a, W_c, W_out, b_out)", "bound": "hbm", "elements": n_params,
+                 "ms": adam_ms, "achieved": adam_bytes / (adam_ms * 1e-3) / 1e9 if adam_ms > 0 else 0.0,
+                 "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                 "frac": adam_bytes / (adam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if adam_ms > 0 else 0.0},
+        "step_is": "fwd(dropout 0.3)+bwd+adam" if a.train_step else "fwd+bwd",
     }
     if not a.no_cpu_baseline:
         del db

@@ -49,7 +49,7 @@ template <> __device__ __forceinline__ float round_elem<uint16_t>(float v) {
 // philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11): counter (c0..c3), key (k0,k1) -> w[4]
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
                                               uint32_t k1, uint32_t (&w)[4]) {
-#pragma unroll
+#pragma unroll 1   // kept as a loop: unrolled, 32 copies of it stop the GEMM epilogue around it from unrolling
   for (int r = 0; r < 10; ++r) {
     if (r > 0) {
       k0 += 0x9E3779B9u;

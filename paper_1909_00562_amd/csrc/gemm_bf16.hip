@@ -154,7 +154,7 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 // loads) go through buffer resources that start at the wave tile's first element, so
 // the row part of an address is a scalar offset, the lane part one register, and rows
 // beyond M are dropped by pointing the lane offset outside the resource instead of branching.
-template <int TM, int TN, bool OUT_BF16, int CH, int EP_LD>
+template <int TM, int TN, bool OUT_BF16, bool DROP, int CH, int EP_LD>
 __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
                                                   int lane, int row0, int col0, int batch, int z) {
   constexpr int WAIT_LGKM_ONLY = 0xC07F;
@@ -207,7 +207,7 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
         for (int c = 0; c < 4; ++c) v[c] = tanhf(v[c]);
       }
       float dact[4] = {1.f - v[0] * v[0], 1.f - v[1] * v[1], 1.f - v[2] * v[2], 1.f - v[3] * v[3]};
-      if (fuse && p.drop_thr) {   // the lane's four columns are one block of the generator (N % 4 == 0)
+      if constexpr (DROP) {       // the lane's four columns are one block of the generator (N % 4 == 0)
         uint32_t w[4];
         dropout_words4(((uint64_t)(row0 + vrow + nrow) * p.N + (uint32_t)(col0 + vcol)) >> 2, p.drop_seed, w);
 #pragma unroll
@@ -257,13 +257,13 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
   }
 }
 
-template <int TM, int TN, bool OUT_BF16, bool VEC, int CH = 32, int EP_LD = 72>
+template <int TM, int TN, bool OUT_BF16, bool VEC, bool DROP, int CH = 32, int EP_LD = 72>
 __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
                                               int lane, int row0, int col0, int batch, int z) {
   static_assert(TN == 2, "64-column wave tiles");
   static_assert(CH == 32 || CH == 16, "chunk of one or half an MFMA tile");
   if constexpr (VEC) {
-    gemm_epilogue_vec<TM, TN, OUT_BF16, CH, EP_LD>(p, acc, region, lane, row0, col0, batch, z);
+    gemm_epilogue_vec<TM, TN, OUT_BF16, DROP, CH, EP_LD>(p, acc, region, lane, row0, col0, batch, z);
     return;
   }
   constexpr int WAIT_LGKM_ONLY = 0xC07F;   // leaves global loads in flight
@@ -328,7 +328,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
         float x = v[c] + bias4[c];
         if (p.act_tanh) x = tanhf(x);
         dact[c] = 1.f - x * x;
-        if (p.drop_thr && gcol + c < p.N) {
+        if (DROP && gcol + c < p.N) {
           const float sc = dropout_mult((uint64_t)grow * p.N + (gcol + c), p.drop_seed, p.drop_thr, p.drop_scale);
           x *= sc;
           dact[c] *= sc;
@@ -381,7 +381,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC>
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   constexpr int NW = WGM * WGN, NT = 64 * NW;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
@@ -542,7 +542,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   }
   // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
-  gemm_epilogue<TM, TN, OUT_BF16, VEC>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
+  gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
 }
 
 
@@ -655,7 +655,7 @@ __device__ __forceinline__ bf16x8_t pp_frag_at(const unsigned char* tile, uint32
 constexpr int PP_EPI_OFF = 2 * PSTAGE;        // epilogue staging behind the two tile stages
 constexpr int PP_SMEM = PP_EPI_OFF + 8 * 4096;
 
-template <bool AKC, bool BKC, bool OUT_BF16, bool VEC>
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_total) {
   constexpr int BM = 256, BN = 256, WGN = 4;
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
@@ -829,16 +829,16 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
       }
     }
     // item done: write it out while the next item's first tile is already in flight
-    gemm_epilogue<TM, TN, OUT_BF16, VEC, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
                                             it.n0 + wn * WN, it.batch, it.z);
     zero_acc();
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC>
+template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP = false>
 static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = 2 * (BM + BN) * ROWB;
-  auto kfn = gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC, OUT_BF16, VEC>;
+  auto kfn = gemm_bf16_kernel<BM, BN, WGM, WGN, AKC, BKC, OUT_BF16, VEC, DROP>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -851,10 +851,10 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   return hipGetLastError();
 }
 
-template <bool AKC, bool BKC, bool OUT_BF16, bool VEC>
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP = false>
 static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = PP_SMEM;
-  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16, VEC>;
+  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16, VEC, DROP>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
@@ -874,6 +874,22 @@ template <bool BIG, bool AKC, bool BKC>
 static hipError_t launch_oriented(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
   const bool obf = g.c_bf16 && g.splits <= 1;
   const bool vec = d.vec_ok != 0;
+  if (d.drop_thr) {   // dropout variants exist for the one product that uses them (both operands reduction-contiguous)
+    if constexpr (AKC && BKC) {
+      if constexpr (BIG) {
+        if (obf) return vec ? launch_pp<true, true, true, true, true>(d, g.batch, st) : launch_pp<true, true, true, false, true>(d, g.batch, st);
+        return vec ? launch_pp<true, true, false, true, true>(d, g.batch, st) : launch_pp<true, true, false, false, true>(d, g.batch, st);
+      } else {
+        if (obf)
+          return vec ? launch_one<128, 128, 2, 2, true, true, true, true, true>(d, g.batch, st)
+                     : launch_one<128, 128, 2, 2, true, true, true, false, true>(d, g.batch, st);
+        return vec ? launch_one<128, 128, 2, 2, true, true, false, true, true>(d, g.batch, st)
+                   : launch_one<128, 128, 2, 2, true, true, false, false, true>(d, g.batch, st);
+      }
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   if constexpr (BIG) {
     if (obf) return vec ? launch_pp<AKC, BKC, true, true>(d, g.batch, st) : launch_pp<AKC, BKC, true, false>(d, g.batch, st);
     return vec ? launch_pp<AKC, BKC, false, true>(d, g.batch, st) : launch_pp<AKC, BKC, false, false>(d, g.batch, st);
