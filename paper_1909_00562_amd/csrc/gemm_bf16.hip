@@ -48,6 +48,7 @@ struct GemmDev {
   int splits;
   float* partial;
   int tiles_m, tiles_n;
+  int group;   // tile rows per group of the persistent kernel's tile walk
   int kper;    // reduction elements per split, multiple of 64
   int vec_ok;  // rows of C (and C_lo, C_dact, gate) allow 8/16-byte vector access
 };
@@ -683,7 +684,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
     Item it;
     it.z = w / nt;
     const int pid = w - it.z * nt;
-    constexpr int GROUP = 8;      // tiles are walked in groups of 8 tile rows
+    const int GROUP = p.group;    // tiles are walked in groups of `group` tile rows
     const int gsize = GROUP * p.tiles_n;
     const int gid = pid / gsize;
     const int first_m = gid * GROUP;
@@ -961,6 +962,9 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   const int bm = big_tile ? 256 : 128;
   d.tiles_m = (g.M + bm - 1) / bm;
   d.tiles_n = (g.N + bm - 1) / bm;
+  // many column tiles: 8 rows x 4 columns of co-resident tiles per XCD share 12 operand panels; few column
+  // tiles (long-reduction products): whole tile rows, so a row panel is consumed in one go (measured 2-3 % faster)
+  d.group = d.tiles_n >= 16 ? 8 : (16 / d.tiles_n < 2 ? 2 : (16 / d.tiles_n > 8 ? 8 : 16 / d.tiles_n));
   const int ktiles = (g.K[0] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
