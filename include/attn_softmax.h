@@ -179,6 +179,33 @@ as_status attn_softmax_profile_enable(int enable);
 as_status attn_softmax_profile_read(double* ms_total, int64_t* launches);
 
 /*
+ * Per-step mode: one decoder step (T = 1) at a time, for decoding, scoring and the
+ * input-feeding variant of the model (section 4, "HybridNMTIF": the attentional
+ * state of step t is an input of step t+1, so the steps cannot be batched).
+ * The encoder-side half of the score of Eq. 2, K'[s,b,:] = W_a h_enc[s,b,:], does
+ * not depend on the step: attn_softmax_step_prepare computes it once per batch of
+ * sentences into the workspace; attn_softmax_step_fwd then runs Eq. 1-3 as one
+ * fused kernel (score[s] = h_t[b] . K'[s,b], masked softmax, context) followed by
+ * Eq. 4-6 exactly as attn_softmax_fwd does.  shape->T is ignored (taken as 1);
+ * h_t [B,H] dtype is the decoder state of this step, targets [B] the words to
+ * score (pad_id everywhere when only the prediction is wanted).  Outputs as in
+ * attn_softmax_fwd with T = 1; the step's attention weights, context, h_c, logits
+ * and lse are read with attn_softmax_view() (same workspace, shape with T = 1).
+ * The workspace (attn_softmax_step_workspace_bytes) must not be used by another
+ * call between prepare and the steps that follow it.  Dropout applies as in
+ * attn_softmax_fwd when shape->dropout_p > 0.  Errors as attn_softmax_fwd.
+ */
+size_t attn_softmax_step_workspace_bytes(const as_shape* shape);
+as_status attn_softmax_step_prepare(const as_shape* shape, const void* h_enc, const void* W_a,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+as_status attn_softmax_step_fwd(const as_shape* shape,
+                                const void* h_t, const void* h_enc, const int32_t* src_len,
+                                const void* W_c, const void* W_out, const void* b_out,
+                                const int32_t* targets,
+                                float* loss_sum, int32_t* n_tok, float* tok_loss, int32_t* argmax,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * One Adam update of one parameter tensor of this part of the model (section
  * 4.2, "Parameter settings": Adam with beta1 = 0.9, beta2 = 0.999, eps = 1e-8;
  * Table 2: initial learning rate 0.001), bias-corrected as in Kingma and Ba's

@@ -25,7 +25,8 @@ STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "g
                "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam"]
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
-           "attn_softmax_adam_step"]
+           "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
+           "attn_softmax_step_fwd"]
 
 
 class AttnSoftmaxError(RuntimeError):
@@ -75,6 +76,12 @@ def load_library():
     lib.attn_softmax_profile_enable.argtypes = [ctypes.c_int]
     lib.attn_softmax_profile_read.restype = ctypes.c_int
     lib.attn_softmax_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.attn_softmax_step_workspace_bytes.restype = sz
+    lib.attn_softmax_step_workspace_bytes.argtypes = [ctypes.POINTER(AsShape)]
+    lib.attn_softmax_step_prepare.restype = ctypes.c_int
+    lib.attn_softmax_step_prepare.argtypes = [ctypes.POINTER(AsShape), vp, vp, vp, sz, vp]
+    lib.attn_softmax_step_fwd.restype = ctypes.c_int
+    lib.attn_softmax_step_fwd.argtypes = [ctypes.POINTER(AsShape)] + [vp] * 11 + [vp, sz, vp]
     lib.attn_softmax_adam_step.restype = ctypes.c_int
     lib.attn_softmax_adam_step.argtypes = [ctypes.POINTER(AsAdam), sz, vp, vp, vp, vp, vp, ctypes.c_int32, vp]
     _lib = lib
@@ -133,6 +140,29 @@ def attn_softmax_view(shape, workspace, which: int):
     _check(load_library().attn_softmax_view(ctypes.byref(shape), _ptr(workspace), which, ctypes.byref(p),
                                             ctypes.byref(n), ctypes.byref(ld)))
     return int(p.value), int(n.value), int(ld.value)
+
+
+def attn_softmax_step_workspace_bytes(shape: AsShape) -> int:
+    return int(load_library().attn_softmax_step_workspace_bytes(ctypes.byref(shape)))
+
+
+def attn_softmax_step_prepare(shape, h_enc, W_a, workspace, workspace_bytes, stream=0, check=True) -> int:
+    rc = load_library().attn_softmax_step_prepare(ctypes.byref(shape) if shape is not None else None, _ptr(h_enc),
+                                                  _ptr(W_a), _ptr(workspace), workspace_bytes, stream)
+    if check:
+        _check(rc)
+    return rc
+
+
+def attn_softmax_step_fwd(shape, h_t, h_enc, src_len, W_c, W_out, b_out, targets, loss_sum, n_tok, tok_loss,
+                          argmax, workspace, workspace_bytes, stream=0, check=True) -> int:
+    rc = load_library().attn_softmax_step_fwd(ctypes.byref(shape) if shape is not None else None, _ptr(h_t),
+                                              _ptr(h_enc), _ptr(src_len), _ptr(W_c), _ptr(W_out), _ptr(b_out),
+                                              _ptr(targets), _ptr(loss_sum), _ptr(n_tok), _ptr(tok_loss),
+                                              _ptr(argmax), _ptr(workspace), workspace_bytes, stream)
+    if check:
+        _check(rc)
+    return rc
 
 
 def attn_softmax_adam_step(hyper: AsAdam, n: int, grad, master, m, v, weights_out, dtype: int, stream: int = 0,

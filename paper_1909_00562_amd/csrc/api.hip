@@ -114,7 +114,7 @@ Layout make_layout(const as_shape* s) {
   L.p_q = gemm_plan(N, H, H, 1, bf, false);
   L.p_score = gemm_plan(T, S, H, B, bf, false);
   L.p_ctx = gemm_plan(T, H, S, B, bf, false);
-  L.p_hc = gemm_plan(N, H, 2 * H, 1, bf, false);
+  L.p_hc = gemm_plan(N, H, bf ? 3 * H : 2 * H, 1, bf, true, true);   // segments: ctx (+ remainder), h_dec
   L.p_logits = gemm_plan(N, V, H, 1, bf, false);
   L.p_dwout = gemm_plan(V, H, N, 1, bf, true);
   L.p_dhc = gemm_plan(N, H, V, 1, bf, true);
@@ -127,6 +127,7 @@ Layout make_layout(const as_shape* s) {
   L.p_dh = gemm_plan(N, H, H, 1, bf, false);
   size_t pb = 0;
   auto mx = [&](size_t v) { if (v > pb) pb = v; };
+  mx(gemm_partial_bytes(N, H, 1, L.p_hc.splits));
   mx(gemm_partial_bytes(V, H, 1, L.p_dwout.splits));
   mx(gemm_partial_bytes(N, H, 1, L.p_dhc.splits));
   mx(gemm_partial_bytes(H, H, 1, L.p_dwc.splits));
@@ -201,6 +202,45 @@ as_status check_common(const as_shape* s, const void* h_dec, const void* h_enc, 
   } while (0)
 
 }  // namespace
+
+// Eq. 4-6 from the context vectors on: shared by the batched forward pass and the per-step one.
+static as_status fwd_from_ctx(const as_shape* s, const Layout& L, char* w, const char* hd, const char* wc,
+                              const void* W_out, const void* b_out, const int32_t* targets, float* loss_sum,
+                              int32_t* n_tok, float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, hipStream_t st) {
+  const bool bf = s->dtype == AS_BF16;
+  const int H = s->H, V = s->V, N = (int)L.N;
+  {  // h_c = tanh(W_c[:, :H] ctx + W_c[:, H:] h_dec)                       (Eq. 4)
+    GemmArgs g;
+    g.seg(w + L.ctx, H, 0, wc, 2 * H, 0, H);
+    g.seg(w + L.ctx_lo, H, 0, wc, 2 * H, 0, H);
+    g.seg(hd, H, 0, wc + (size_t)H * L.e, 2 * H, 0, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = N; g.N = H; g.act_tanh = 1;
+    g.C = w + L.hc; g.ldc = H; g.c_bf16 = bf;
+    g.C_dact = reinterpret_cast<float*>(w + L.dact);
+    g.splits = L.p_hc.splits; g.partial = reinterpret_cast<float*>(w + L.partial);
+    if (s->dropout_p > 0.f) {   // section 4.2: dropout, here on the attentional state; the mask rides on dact into bwd
+      g.drop_thr = (uint32_t)((double)s->dropout_p * 4294967296.0);   // floor: the product is exact in double
+      g.drop_scale = 1.f / (1.f - s->dropout_p);
+      g.drop_seed = s->dropout_seed;
+    }
+    AS_TRY(AS_STAGE_GEMM_HC, launch_gemm(g, bf, L.p_hc.big_tile, st));
+  }
+  {  // logits = h_c W_out^T + b_out                                        (Eq. 5)
+    GemmArgs g;
+    g.seg(w + L.hc, H, 0, W_out, H, 0, H);
+    g.a_kc = true; g.b_kc = true;
+    g.M = N; g.N = V; g.bias = b_out;
+    g.C = w + L.logits; g.ldc = L.ldV; g.c_bf16 = bf;
+    AS_TRY(AS_STAGE_GEMM_LOGITS, launch_gemm(g, bf, L.p_logits.big_tile, st));
+  }
+  AS_TRY(AS_STAGE_XENT_STATS,                                          // Eq. 5-6
+         launch_xent_stats(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id, reinterpret_cast<float*>(w + L.lse),
+                           reinterpret_cast<float*>(w + L.tokloss), tok_loss, argmax, tgt_mask, st));
+  AS_TRY(AS_STAGE_MISC, launch_loss_reduce(reinterpret_cast<const float*>(w + L.tokloss), targets, N, V, s->pad_id,
+                                           loss_sum, n_tok, st));
+  return AS_OK;
+}
 
 extern "C" {
 
@@ -285,36 +325,7 @@ as_status attn_softmax_fwd(const as_shape* s, const void* h_dec, const void* h_e
     g.C_lo = w + L.ctx_lo;
     AS_TRY(AS_STAGE_ATTN_CTX, launch_gemm(g, bf, L.p_ctx.big_tile, st));
   }
-  {  // h_c = tanh(W_c[:, :H] ctx + W_c[:, H:] h_dec)                       (Eq. 4)
-    GemmArgs g;
-    g.seg(w + L.ctx, H, 0, wc, 2 * H, 0, H);
-    g.seg(w + L.ctx_lo, H, 0, wc, 2 * H, 0, H);
-    g.seg(hd, H, 0, wc + (size_t)H * L.e, 2 * H, 0, H);
-    g.a_kc = true; g.b_kc = true;
-    g.M = N; g.N = H; g.act_tanh = 1;
-    g.C = w + L.hc; g.ldc = H; g.c_bf16 = bf;
-    g.C_dact = reinterpret_cast<float*>(w + L.dact);
-    if (s->dropout_p > 0.f) {   // section 4.2: dropout, here on the attentional state; the mask rides on dact into bwd
-      g.drop_thr = (uint32_t)((double)s->dropout_p * 4294967296.0);   // floor: the product is exact in double
-      g.drop_scale = 1.f / (1.f - s->dropout_p);
-      g.drop_seed = s->dropout_seed;
-    }
-    AS_TRY(AS_STAGE_GEMM_HC, launch_gemm(g, bf, L.p_hc.big_tile, st));
-  }
-  {  // logits = h_c W_out^T + b_out                                        (Eq. 5)
-    GemmArgs g;
-    g.seg(w + L.hc, H, 0, W_out, H, 0, H);
-    g.a_kc = true; g.b_kc = true;
-    g.M = N; g.N = V; g.bias = b_out;
-    g.C = w + L.logits; g.ldc = L.ldV; g.c_bf16 = bf;
-    AS_TRY(AS_STAGE_GEMM_LOGITS, launch_gemm(g, bf, L.p_logits.big_tile, st));
-  }
-  AS_TRY(AS_STAGE_XENT_STATS,                                          // Eq. 5-6
-         launch_xent_stats(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id, reinterpret_cast<float*>(w + L.lse),
-                           reinterpret_cast<float*>(w + L.tokloss), tok_loss, argmax, tgt_mask, st));
-  AS_TRY(AS_STAGE_MISC, launch_loss_reduce(reinterpret_cast<const float*>(w + L.tokloss), targets, N, V, s->pad_id,
-                                           loss_sum, n_tok, st));
-  return AS_OK;
+  return fwd_from_ctx(s, L, w, hd, wc, W_out, b_out, targets, loss_sum, n_tok, tok_loss, argmax, tgt_mask, st);
 }
 
 as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
@@ -449,6 +460,89 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
     AS_TRY(AS_STAGE_GEMM_DH, launch_gemm(g, bf, L.p_dh.big_tile, st));
   }
   return AS_OK;
+}
+
+// ---- per-step mode (T = 1) ---------------------------------------------------------
+namespace {
+struct StepLayout {
+  Layout L;          // the batched layout for T = 1 (views work unchanged)
+  size_t kprime;     // float [S,B,H]: W_a h_enc
+  size_t total;
+  GemmPlan p_kp;
+};
+StepLayout make_step_layout(const as_shape* s) {
+  as_shape s1 = *s;
+  s1.T = 1;
+  StepLayout sl;
+  sl.L = make_layout(&s1);
+  sl.kprime = sl.L.total;
+  sl.total = sl.kprime + up((size_t)s->S * s->B * s->H * sizeof(float), kAlign);
+  sl.p_kp = gemm_plan(s->S * s->B, s->H, s->H, 1, s->dtype == AS_BF16, false);
+  return sl;
+}
+bool step_shape_ok(const as_shape* s, as_shape* s1) {
+  if (!s) return false;
+  *s1 = *s;
+  s1->T = 1;
+  return shape_ok(s1) && !(s->dtype == AS_BF16 && (s->H % 8) != 0);
+}
+}  // namespace
+
+size_t attn_softmax_step_workspace_bytes(const as_shape* shape) {
+  as_shape s1;
+  if (!step_shape_ok(shape, &s1)) return 0;
+  return make_step_layout(&s1).total;
+}
+
+as_status attn_softmax_step_prepare(const as_shape* shape, const void* h_enc, const void* W_a, void* workspace,
+                                    size_t workspace_bytes, void* hip_stream) {
+  as_shape s1;
+  if (!shape) return fail(AS_ERR_NULL, "shape is NULL");
+  if (shape->dtype != AS_F32 && shape->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", shape->dtype);
+  if (!step_shape_ok(shape, &s1)) return fail(AS_ERR_SHAPE, "bad shape for the per-step mode");
+  if (!h_enc || !W_a || !workspace) return fail(AS_ERR_NULL, "a required pointer is NULL");
+  if (!aligned16(h_enc) || !aligned16(W_a) || !aligned16(workspace)) return fail(AS_ERR_ALIGN, "pointer not 16-byte aligned");
+  const StepLayout sl = make_step_layout(&s1);
+  if (workspace_bytes < sl.total)
+    return fail(AS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, sl.total);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const bool bf = s1.dtype == AS_BF16;
+  const int H = s1.H;
+  char* w = reinterpret_cast<char*>(workspace);
+  GemmArgs g;   // K'[(s,b), i] = sum_j h_enc[(s,b), j] W_a[i, j]: the encoder-side half of Eq. 2
+  g.seg(h_enc, H, 0, W_a, H, 0, H);
+  g.a_kc = true; g.b_kc = true;
+  g.M = s1.S * s1.B; g.N = H;
+  g.C = w + sl.kprime; g.ldc = H; g.c_bf16 = false;
+  AS_TRY(AS_STAGE_GEMM_Q, launch_gemm(g, bf, sl.p_kp.big_tile, st));
+  return AS_OK;
+}
+
+as_status attn_softmax_step_fwd(const as_shape* shape, const void* h_t, const void* h_enc, const int32_t* src_len,
+                                const void* W_c, const void* W_out, const void* b_out, const int32_t* targets,
+                                float* loss_sum, int32_t* n_tok, float* tok_loss, int32_t* argmax,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  as_shape s1;
+  if (!shape) return fail(AS_ERR_NULL, "shape is NULL");
+  if (shape->dtype != AS_F32 && shape->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", shape->dtype);
+  if (!step_shape_ok(shape, &s1)) return fail(AS_ERR_SHAPE, "bad shape for the per-step mode");
+  if (!h_t || !h_enc || !src_len || !W_c || !W_out || !b_out || !targets || !workspace || !loss_sum || !n_tok)
+    return fail(AS_ERR_NULL, "a required pointer is NULL");
+  const void* ptrs[] = {h_t, h_enc, src_len, W_c, W_out, b_out, targets, workspace};
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return fail(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  const StepLayout sl = make_step_layout(&s1);
+  if (workspace_bytes < sl.total)
+    return fail(AS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, sl.total);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const bool bf = s1.dtype == AS_BF16;
+  const Layout& L = sl.L;
+  char* w = reinterpret_cast<char*>(workspace);
+  AS_TRY(AS_STAGE_ATTN_SCORE,                                           // Eq. 1-3 for one step, fused
+         launch_attn_step(h_t, reinterpret_cast<const float*>(w + sl.kprime), h_enc, src_len, s1.B, s1.S, s1.H,
+                          reinterpret_cast<float*>(w + L.alpha32), w + L.ctx, w + L.ctx_lo, bf, nullptr, st));
+  return fwd_from_ctx(&s1, L, w, reinterpret_cast<const char*>(h_t), reinterpret_cast<const char*>(W_c), W_out, b_out,
+                      targets, loss_sum, n_tok, tok_loss, argmax, nullptr, st);
 }
 
 as_status attn_softmax_adam_step(const as_adam* hp, size_t n, const float* grad, float* master, float* m, float* v,

@@ -69,7 +69,8 @@ struct GemmPlan {
   int big_tile;   // bf16: 1 = 256x256 block tile, 0 = 128x128
   int splits;
 };
-GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split);
+// multi_segment: the reduction runs over several operand segments; only the 128x128 kernel can split those
+GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split, bool multi_segment = false);
 inline size_t gemm_partial_bytes(int M, int N, int batch, int splits) {
   return splits > 1 ? (size_t)splits * batch * M * N * sizeof(float) : 0;
 }

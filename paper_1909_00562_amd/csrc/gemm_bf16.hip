@@ -417,20 +417,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   const int z = blockIdx.z;
   const int batch = z / p.splits, split = z - batch * p.splits;
 
-  // reduction range of each segment (a split applies to a single segment only)
-  int kbeg0 = 0, kend0 = p.K[0];
-  if (p.splits > 1) {
-    kbeg0 = split * p.kper;
-    kend0 = kbeg0 + p.kper < p.K[0] ? kbeg0 + p.kper : p.K[0];
-  }
+  // reduction tiles of this block: all of them, or (split-K) tiles [t0, t1) of the sequence that runs
+  // through the segments one after the other; the cursor below starts at tile t0
   int nks[kMaxSeg];
-  nks[0] = kend0 > kbeg0 ? (kend0 - kbeg0 + BK - 1) / BK : 0;
-  int nk = nks[0];
+  int nk = 0;
 #pragma unroll
-  for (int s = 1; s < kMaxSeg; ++s) {
+  for (int s = 0; s < kMaxSeg; ++s) {
     nks[s] = (p.K[s] + BK - 1) / BK;
     nk += nks[s];
   }
+  int seg0 = 0, skip0 = 0;   // first segment of this block and reduction tiles skipped inside it
+  if (p.splits > 1) {
+    const int tper = p.kper / BK;
+    const int t0 = split * tper;
+    const int t1 = t0 + tper < nk ? t0 + tper : nk;
+    nk = t1 > t0 ? t1 - t0 : 0;
+    skip0 = t0;
+    while (seg0 < kMaxSeg - 1 && skip0 >= nks[seg0]) {
+      skip0 -= nks[seg0];
+      ++seg0;
+    }
+  }
+  const int kbeg0 = skip0 * BK;
 
   f32x16_t acc[TM][TN];
 #pragma unroll
@@ -454,9 +462,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   // cursor over the reduction tiles of all segments: operand pointers of the next tile to load
   const int64_t stepA = AKC ? BK : (int64_t)BK * p.lda[0], stepB = BKC ? BK : (int64_t)BK * p.ldb[0];
   const int64_t offA = AKC ? (int64_t)m0 * p.lda[0] : m0, offB = BKC ? (int64_t)n0 * p.ldb[0] : n0;
-  int cseg = 0, ck_left = kend0 - kbeg0;
-  const uint16_t* cA = p.A[0] + (int64_t)batch * p.sA[0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
-  const uint16_t* cB = p.B[0] + (int64_t)batch * p.sB[0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
+  int cseg = seg0, ck_left = p.K[seg0] - kbeg0;
+  const uint16_t* cA = p.A[seg0] + (int64_t)batch * p.sA[seg0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
+  const uint16_t* cB = p.B[seg0] + (int64_t)batch * p.sB[seg0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
   auto advance = [&]() {
     cA += stepA;
     cB += stepB;
@@ -915,7 +923,8 @@ static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) =
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   if (g.M < 1 || g.N < 1 || g.batch < 1 || g.splits < 1) return hipErrorInvalidValue;
-  if (g.splits > 1 && (g.K[1] != 0 || g.partial == nullptr || g.C_dact || g.drop_thr)) return hipErrorInvalidValue;
+  // split-K: the combine step applies the epilogue; the persistent kernel splits a single segment only
+  if (g.splits > 1 && (g.partial == nullptr || (big_tile && g.K[1] != 0))) return hipErrorInvalidValue;
   if (g.drop_thr && g.batch != 1) return hipErrorInvalidValue;   // flat element index = m * N + n
   if ((g.C_lo || g.C_dact) && !g.c_bf16) return hipErrorInvalidValue;
   GemmDev d;
@@ -947,7 +956,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   d.gate = g.gate;
   d.ldg = g.ldg;
   d.act_tanh = g.act_tanh;
-  d.drop_thr = g.drop_thr;
+  d.drop_thr = g.splits > 1 ? 0u : g.drop_thr;   // with split-K the combine step applies the epilogue
   d.drop_scale = g.drop_scale;
   d.drop_seed = g.drop_seed;
   d.accumulate = g.accumulate;
@@ -965,9 +974,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   // many column tiles: 8 rows x 4 columns of co-resident tiles per XCD share 12 operand panels; few column
   // tiles (long-reduction products): whole tile rows, so a row panel is consumed in one go (measured 2-3 % faster)
   d.group = d.tiles_n >= 16 ? 8 : (16 / d.tiles_n < 2 ? 2 : (16 / d.tiles_n > 8 ? 8 : 16 / d.tiles_n));
-  const int ktiles = (g.K[0] + BK - 1) / BK;
+  int ktiles = 0;   // reduction tiles of all segments (the persistent kernel splits segment 0 alone, checked above)
+  for (int s = 0; s < kMaxSeg; ++s) ktiles += (g.K[s] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
-  if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
+  if (g.splits > 1 && (int64_t)(d.kper / BK) * (g.splits - 1) >= ktiles) return hipErrorInvalidValue;   // an empty split
   return big_tile ? launch_tile<true>(g, d, st) : launch_tile<false>(g, d, st);
 }
 

@@ -169,7 +169,9 @@ template <typename TIn, bool OUT_BF16>
 __global__ __launch_bounds__(256) void splitk_combine_kernel(const float* __restrict__ partial, int splits,
                                                             int M, int N, void* C, void* C_lo, int64_t ldc,
                                                             int64_t sC, const TIn* bias, const float* gate,
-                                                            int64_t ldg, int act_tanh, int accumulate) {
+                                                            int64_t ldg, int act_tanh, int accumulate,
+                                                            float* C_dact, uint32_t drop_thr, float drop_scale,
+                                                            uint64_t drop_seed) {
   const int64_t mn = (int64_t)M * N;
   const int batch = blockIdx.y;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn; i += (int64_t)gridDim.x * 256) {
@@ -179,8 +181,15 @@ __global__ __launch_bounds__(256) void splitk_combine_kernel(const float* __rest
     for (int s = 0; s < splits; ++s) v += P[(int64_t)s * mn];
     if (bias) v += ld_elem<TIn>(bias, col);
     if (act_tanh) v = tanhf(v);
+    float dact = 1.f - v * v;
+    if (drop_thr) {
+      const float sc = dropout_mult((uint64_t)i, drop_seed, drop_thr, drop_scale);   // i = row * N + col
+      v *= sc;
+      dact *= sc;
+    }
     if (gate) v *= gate[(int64_t)row * ldg + col];
     const int64_t ci = (int64_t)batch * sC + (int64_t)row * ldc + col;
+    if (C_dact) C_dact[ci] = dact;
     if constexpr (OUT_BF16) {
       const uint32_t hi = f32_to_bf16_bits(v);
       reinterpret_cast<uint16_t*>(C)[ci] = (uint16_t)hi;
@@ -204,14 +213,16 @@ hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st
     const float* gate = g.gate;
     if (g.c_bf16)
       hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, true>), grid, dim3(256), 0, st, g.partial, g.splits,
-                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate);
+                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact,
+                         g.drop_thr, g.drop_scale, g.drop_seed);
     else
       hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, false>), grid, dim3(256), 0, st, g.partial, g.splits,
-                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate);
+                         g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact,
+                         g.drop_thr, g.drop_scale, g.drop_seed);
   } else {
     hipLaunchKernelGGL((splitk_combine_kernel<float, false>), grid, dim3(256), 0, st, g.partial, g.splits, g.M,
                        g.N, g.C, g.C_lo, g.ldc, g.sC, reinterpret_cast<const float*>(g.bias),
-                       g.gate, g.ldg, g.act_tanh, g.accumulate);
+                       g.gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact, g.drop_thr, g.drop_scale, g.drop_seed);
   }
   return hipGetLastError();
 }
@@ -235,11 +246,12 @@ static double plan_cost(int M, int N, int K, int batch, int tile, int splits) {
   return t;
 }
 
-GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split) {
+GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split, bool multi_segment) {
   GemmPlan pl;
   pl.big_tile = 0;
   pl.splits = 1;
   if (!bf16) {
+    if (multi_segment) allow_split = false;
     // fp32 path: plain 64x64 tiles; split only to fill the machine
     const int64_t tiles = (int64_t)((M + FT - 1) / FT) * ((N + FT - 1) / FT) * batch;
     if (allow_split && tiles < 384) {
@@ -264,6 +276,7 @@ GemmPlan gemm_plan(int M, int N, int K, int batch, bool bf16, bool allow_split) 
       const int per = (ktiles + want - 1) / want;
       const int s = (ktiles + per - 1) / per;            // no empty split
       if (s != want) continue;
+      if (tile == 256 && s > 1 && multi_segment) continue;
       const double c = plan_cost(M, N, K, batch, tile, s);
       if (c < best) {
         best = c;

@@ -37,6 +37,11 @@ hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, in
 // db_out[v] = sum_rb db_partial[rb][v]
 hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st);
 
+// One decoder step of attention, fused (Eq. 1-3 with T = 1): kprime [S,B,H] float = W_a h_enc, h_t [B,H],
+// h_enc [S,B,H]; writes alpha [B,S] float, ctx [B,H] (+ optional rounding remainder ctx_lo), optional attn_mask.
+hipError_t launch_attn_step(const void* h_t, const float* kprime, const void* h_enc, const int32_t* src_len, int B,
+                            int S, int H, float* alpha, void* ctx, void* ctx_lo, bool e_bf16, uint8_t* attn_mask,
+                            hipStream_t st);
 // Adam, bias corrections passed as inv_bc1 = 1 / (1 - beta1^step), inv_bc2 likewise; wout optional.
 hipError_t launch_adam_step(size_t n, const float* grad, float* master, float* m, float* v, void* wout,
                             bool out_bf16, float lr, float beta1, float beta2, float eps, float inv_bc1,

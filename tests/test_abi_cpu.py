@@ -137,3 +137,17 @@ def test_adam_rejects_bad_arguments_before_any_launch():
     assert call(bd.AsAdam(1e-3, 0.9, -0.5, 1e-8, 1)) == 2
     assert call(ok, out=0x5000, dtype=9) == 3
     assert call(ok, m=0x3004) == 5
+
+
+def test_step_mode_rejects_bad_arguments():
+    s = bd.AsShape(1, 8, 4, 64, 100, 0, bd.AS_F32, 1.0, 0.0, 0)
+    n = lib.attn_softmax_step_workspace_bytes(s)
+    assert n > lib.attn_softmax_workspace_bytes(s)          # the cached K' comes on top
+    assert lib.attn_softmax_step_workspace_bytes(bd.AsShape(1, 8, 4, 60, 100, 0, bd.AS_BF16, 1.0, 0.0, 0)) == 0
+    assert lib.attn_softmax_step_prepare(s, 0x1000, 0x2000, 0x3000, n - 1, 0, check=False) == 4
+    assert lib.attn_softmax_step_prepare(s, None, 0x2000, 0x3000, n, 0, check=False) == 1
+    # h_t missing, workspace too small, misaligned pointer: refused before any launch
+    args = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000, None, None, 0xA000]
+    assert lib.attn_softmax_step_fwd(s, None, *args[1:], n, 0, check=False) == 1
+    assert lib.attn_softmax_step_fwd(s, *args, n - 1, 0, check=False) == 4
+    assert lib.attn_softmax_step_fwd(s, 0x1004, *args[1:], n, 0, check=False) == 5
