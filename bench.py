@@ -21,6 +21,8 @@ cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
 adam       = the fused Adam update of the four parameter tensors (outside the timed
              steps unless --train-step): 30 bytes per element (bf16 storage copy)
              or 32 (f32) against the HBM peak
+per_step   = the per-step mode (T = 1) at the paper's model size, outside the timed steps: microseconds
+             per decoder step of attn_softmax_fwd called with T = 1 and of attn_softmax_step_fwd
 --train-step makes a step = forward with dropout 0.3 + backward + Adam on the four
              parameter tensors (the headline metric stays forward + backward)
 """
@@ -87,6 +89,44 @@ def cpu_baseline(inp, budget_s: float = 20.0):
             "sample": f"float64 numpy oracle fwd+bwd on sentences 0..{n - 1} of the {inp.name} batch "
                       f"({tokens} non-pad tokens, {inp.T * n} positions) in {dt:.2f} s",
             "positions_per_s": inp.T * n / dt}
+
+
+def per_step_probe(lib, torch, B=128, S=50, H=1024, V=32000, iters=200):
+    """Per-step mode (one decoder step, T = 1) at the paper's model size: microseconds per step of the general
+    forward entry point called with T = 1 and of the step entry point (cached encoder-side score half, fused
+    attention kernel), and the step's algorithmic HBM bytes (K' float + h_enc + W_c + W_out read, logits
+    written and read once) against the HBM peak."""
+    from synth_inputs import make_custom
+    from paper_1909_00562_amd import binding as bd
+    inp = make_custom(T=1, S=S, B=B, H=H, V=V, seed=11, dtype="bf16")
+    db = lib.DeviceBatch(inp)
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        db.sync()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        db.sync()
+        return (time.perf_counter() - t0) / iters * 1e6
+
+    us_general = timed(db.fwd)
+    sh = bd.AsShape(1, S, B, H, V, inp.pad_id, bd.AS_BF16, 1.0, 0.0, 0)
+    nbytes = lib.attn_softmax_step_workspace_bytes(sh)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=db.dev)
+    h_t, tgt = db.h_dec[0].clone(), db.targets[0].clone()
+    tok = torch.zeros(B, dtype=torch.float32, device=db.dev)
+    amax = torch.zeros(B, dtype=torch.int32, device=db.dev)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    lib.attn_softmax_step_prepare(sh, db.h_enc, db.W_a, ws, nbytes, st)
+    us_step = timed(lambda: lib.attn_softmax_step_fwd(sh, h_t, db.h_enc, db.src_len, db.W_c, db.W_out, db.b_out, tgt,
+                                                      db.loss_sum, db.n_tok, tok, amax, ws, nbytes, st))
+    bytes_step = S * B * H * (4 + 2) + 2 * H * H * 2 + V * H * 2 + 2 * B * V * 2
+    return {"workload": f"T=1 B={B} S={S} H={H} V={V} bf16", "us_fwd_T1_general": us_general,
+            "us_step_fwd": us_step, "bound": "hbm", "bytes_per_step": bytes_step,
+            "achieved": bytes_step / (us_step * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": bytes_step / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBS}
 
 
 def main():
@@ -240,9 +280,11 @@ def main():
                  "frac": adam_bytes / (adam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if adam_ms > 0 else 0.0},
         "step_is": "fwd(dropout 0.3)+bwd+adam" if a.train_step else "fwd+bwd",
     }
+    del adam_state
+    del db
+    torch.cuda.empty_cache()
+    out["per_step"] = per_step_probe(lib, torch)
     if not a.no_cpu_baseline:
-        del db
-        torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(out))
 
