@@ -844,6 +844,268 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
   }
 }
 
+// ---- the same kernel with 32-wide reduction sub-tiles in a ring of four LDS slots ----
+// Three sub-tiles are in flight instead of one tile, so a load has about 2.5 sub-tile
+// periods to land instead of one tile period; the price is a barrier per 16 MFMAs of a
+// wave instead of per 32, and 64-byte instead of 128-byte global row segments.
+constexpr int RK = 32;                       // reduction elements per sub-tile
+constexpr int RTILE = 256 * RK * 2;          // bytes of one operand sub-tile (16 KiB)
+constexpr int RSLOT = 2 * RTILE;
+constexpr int RING_EPI_OFF = 4 * RSLOT;
+constexpr int RING_SMEM = RING_EPI_OFF + 8 * 4096;
+
+// wave-wide direct loads of one operand sub-tile: 16 loads of 1 KiB, two per wave (8 waves)
+template <bool KC>
+struct RingLoader {
+  uint32_t voff[2];
+  int kpos;
+  __device__ __forceinline__ void init(int64_t ld, int rows_left, int wave, int lane) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int g = wave + 8 * j;
+      if constexpr (KC) {
+        // group g = rows 16g .. 16g+15 (64-byte rows); LDS slot `lane` = row lane/4, physical chunk lane%4;
+        // chunks are swizzled with (row >> 2) & 3 so that 16 consecutive rows of one chunk cover all 64 banks
+        const int row = g * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((lane >> 4) & 3);
+        if (j == 0) kpos = chunk * 8;
+        voff[j] = row < rows_left ? (uint32_t)(((int64_t)row * ld + chunk * 8) * 2) : kOob;
+      } else {
+        const int k = 2 * g + (lane >> 5);
+        const int pc = lane & 31;
+        const int seg = (pc >> 2) ^ (((wave & 1) << 1) + (lane >> 5));   // physical ^ (k & 3)
+        const int col = (seg * 4 + (pc & 3)) * 8;
+        if (j == 0) kpos = k;                                      // load j covers k-row kpos + 16 j
+        voff[j] = col < rows_left ? (uint32_t)(((int64_t)k * ld + col) * 2) : kOob;
+      }
+    }
+  }
+  __device__ __forceinline__ void load(const __amdgpu_buffer_rsrc_t& rs, int k_left, unsigned char* lds_tile,
+                                       int wave) const {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const bool ok = KC ? kpos < k_left : kpos + 16 * j < k_left;
+      const uint32_t off = ok ? voff[j] : kOob;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void_t*)(lds_tile + (wave + 8 * j) * 1024), 16, off, 0, 0, 0);
+    }
+  }
+};
+template <bool KC>
+__device__ __forceinline__ uint32_t ring_frag_base(int row0, int lane) {
+  if constexpr (KC) {
+    const int row = row0 + (lane & 31);
+    const int chunk0 = (lane >> 5) ^ ((row >> 2) & 3);
+    return (uint32_t)(row * (RK * 2) + (chunk0 << 4));    // step kk: XOR (kk << 5), as in the 64-wide tiles
+  } else {
+    return pp_frag_base<false>(row0, lane);               // same [k][256 columns] layout, 32 k-rows
+  }
+}
+
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP>
+__global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work_total) {
+  constexpr int BM = 256, BN = 256, WGN = 4;
+  constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
+  extern __shared__ __align__(1024) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const bool groupB = wave >= 4;
+
+  // Work items are numbered z-major (z = batch * splits + split), tile-minor; consecutive
+  // blocks go round-robin to the 8 XCDs, so XCD x owns a contiguous run of items and
+  // its blocks take them interleaved: co-resident blocks work on neighbouring tiles and
+  // share operand panels in their XCD's L2.
+  const int nt = p.tiles_m * p.tiles_n;
+  const int xcd = blockIdx.x & 7, bidx = blockIdx.x >> 3, nbx = gridDim.x >> 3;
+  const int wper = work_total >> 3, wrem = work_total & 7;
+  const int wbeg = xcd * wper + (xcd < wrem ? xcd : wrem);
+  const int wend = wbeg + wper + (xcd < wrem ? 1 : 0);
+
+  struct Item {
+    int m0, n0, batch, z, kbeg, kend;
+  };
+  auto get_item = [&](int w) {   // w in [wbeg, wend)
+    Item it;
+    it.z = w / nt;
+    const int pid = w - it.z * nt;
+    const int GROUP = p.group;    // tiles are walked in groups of `group` tile rows
+    const int gsize = GROUP * p.tiles_n;
+    const int gid = pid / gsize;
+    const int first_m = gid * GROUP;
+    const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
+    const int in_g = pid - gid * gsize;
+    it.m0 = (first_m + in_g % gm) * BM;
+    it.n0 = (in_g / gm) * BN;
+    it.batch = it.z / p.splits;
+    const int split = it.z - it.batch * p.splits;
+    it.kbeg = 0;
+    it.kend = p.K[0];
+    if (p.splits > 1) {
+      it.kbeg = split * p.kper;
+      it.kend = it.kbeg + p.kper < p.K[0] ? it.kbeg + p.kper : p.K[0];
+    }
+    return it;
+  };
+  int nk_rest = 0;   // reduction tiles of all segments but the first
+#pragma unroll
+  for (int s = 1; s < kMaxSeg; ++s) nk_rest += (p.K[s] + RK - 1) / RK;
+
+  f32x16_t acc[TM][TN];
+  auto zero_acc = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  };
+  zero_acc();
+
+  // ---- load stream: cursor over (item, segment, reduction tile) --------------------
+  RingLoader<AKC> la;
+  RingLoader<BKC> lb;
+  const int64_t stepA = AKC ? RK : (int64_t)RK * p.lda[0], stepB = BKC ? RK : (int64_t)RK * p.ldb[0];
+  int lw = wbeg + bidx;        // work item the cursor is in
+  bool lvalid = lw < wend;     // false once every tile of this block has been issued
+  int cseg = 0, ck_left = 0;
+  const uint16_t *cA = nullptr, *cB = nullptr;
+  int64_t offA = 0, offB = 0;
+  int lbatch = 0;
+  auto enter_item = [&]() {    // cursor to the first reduction tile of item lw
+    const Item it = get_item(lw);
+    la.init(p.lda[0], p.M - it.m0, wave, lane);
+    lb.init(p.ldb[0], p.N - it.n0, wave, lane);
+    offA = AKC ? (int64_t)it.m0 * p.lda[0] : it.m0;
+    offB = BKC ? (int64_t)it.n0 * p.ldb[0] : it.n0;
+    lbatch = it.batch;
+    cseg = 0;
+    ck_left = it.kend - it.kbeg;
+    cA = p.A[0] + (int64_t)lbatch * p.sA[0] + offA + (AKC ? it.kbeg : (int64_t)it.kbeg * p.lda[0]);
+    cB = p.B[0] + (int64_t)lbatch * p.sB[0] + offB + (BKC ? it.kbeg : (int64_t)it.kbeg * p.ldb[0]);
+  };
+  auto advance = [&]() {
+    cA += stepA;
+    cB += stepB;
+    ck_left -= RK;
+    if (ck_left <= 0) {
+      do { ++cseg; } while (cseg < kMaxSeg && p.K[cseg] <= 0);
+      if (cseg < kMaxSeg) {
+        cA = p.A[cseg] + (int64_t)lbatch * p.sA[cseg] + offA;
+        cB = p.B[cseg] + (int64_t)lbatch * p.sB[cseg] + offB;
+        ck_left = p.K[cseg];
+      } else {
+        lw += nbx;
+        lvalid = lw < wend;
+        if (lvalid) enter_item();
+      }
+    }
+  };
+  auto issue = [&](int slot) {   // this wave's four loads of the sub-tile under the cursor
+    unsigned char* as = smem + slot * RSLOT;
+    la.load(make_rsrc(cA), ck_left, as, wave);
+    lb.load(make_rsrc(cB), ck_left, as + RTILE, wave);
+    advance();
+  };
+  bf16x8_t af[2][TM], bfr[2][TN];
+  uint32_t abase[TM], bbase[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) abase[i] = ring_frag_base<AKC>(wm * WM + i * 32, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bbase[j] = ring_frag_base<BKC>(wn * WN + j * 32, lane);
+  auto read_pair = [&](int slot) {   // fragments of both reduction steps of a sub-tile
+    const unsigned char* as = smem + slot * RSLOT;
+    const unsigned char* bs = as + RTILE;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {   // in the order the MFMAs consume them
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag_at<BKC>(bs, bbase[j], h);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[h][i] = pp_frag_at<AKC>(as, abase[i], h);
+    }
+  };
+  auto mfma_pair = [&]() {   // 16 MFMAs from the fragment registers
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto tile_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  constexpr int WAIT_ALL = 0;        // s_waitcnt vmcnt(0) expcnt(0) lgkmcnt(0)
+
+  if (!lvalid) return;               // more blocks than work items: nothing to do (whole block leaves)
+  enter_item();
+  issue(0);
+  if (lvalid) issue(1);
+  if (lvalid) issue(2);
+  __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+  tile_barrier();                                   // barrier 0: sub-tiles 0..2 are in LDS
+
+  // Per sub-tile s (slot s & 3): M(s) = 12 fragment reads + this wave's 4 loads of sub-tile s+3 (into the slot
+  // sub-tile s-1 has left: every wave is past barrier s-1 there), C(s) = 16 MFMAs.  Group A takes barrier s after
+  // C(s), group B after M(s), so B runs one phase behind A.  Before barrier s a wave has its own loads of sub-tile
+  // s+1 in LDS; the eight younger ones (s+2, s+3) stay in flight: a load has about 2.5 sub-tile periods to land.
+  constexpr int WAIT_BUT_8 = 0x0078;  // vmcnt(8) lgkmcnt(0)
+  int g = 0;                                        // sub-tiles done: slot = g & 3
+  for (int cw = wbeg + bidx; cw < wend; cw += nbx) {
+    const Item it = get_item(cw);
+    const int nk = (it.kend - it.kbeg + RK - 1) / RK + nk_rest;
+    for (int t = 0; t < nk; ++t, ++g) {
+      const int slot = g & 3;
+      read_pair(slot);                              // M
+      const bool more = lvalid;                     // the cursor still has sub-tiles: the in-flight count below holds
+      if (lvalid) issue((g + 3) & 3);
+      if (groupB) {
+        if (more) __builtin_amdgcn_s_waitcnt(WAIT_BUT_8); else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        tile_barrier();                             // every wave is done reading this slot
+      }
+      mfma_pair();                                  // C
+      if (!groupB) {
+        if (more) __builtin_amdgcn_s_waitcnt(WAIT_BUT_8); else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        tile_barrier();
+      }
+    }
+    // item done: write it out while the next item's first sub-tiles are already in flight
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, acc, smem + RING_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
+                                            it.n0 + wn * WN, it.batch, it.z);
+    zero_acc();
+  }
+}
+
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC>
+static hipError_t launch_ring(const GemmDev& d, int batch, hipStream_t st) {
+  constexpr int smem = RING_SMEM;
+  auto kfn = gemm_bf16_ring_kernel<AKC, BKC, OUT_BF16, VEC, false>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int work_total = d.tiles_m * d.tiles_n * batch * d.splits;
+  int blocks = work_total < 256 ? (work_total + 7) / 8 * 8 : 256;
+  hipLaunchKernelGGL(kfn, dim3(blocks), dim3(512), smem, st, d, work_total);
+  return hipGetLastError();
+}
+template <bool AKC, bool BKC>
+static hipError_t launch_ring_oriented(const GemmArgs& g, const GemmDev& d, hipStream_t st) {
+  const bool obf = g.c_bf16 && g.splits <= 1;
+  const bool vec = d.vec_ok != 0;
+  if (obf) return vec ? launch_ring<AKC, BKC, true, true>(d, g.batch, st) : launch_ring<AKC, BKC, true, false>(d, g.batch, st);
+  return vec ? launch_ring<AKC, BKC, false, true>(d, g.batch, st) : launch_ring<AKC, BKC, false, false>(d, g.batch, st);
+}
+
 template <int BM, int BN, int WGM, int WGN, bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP = false>
 static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = 2 * (BM + BN) * ROWB;
@@ -978,6 +1240,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   for (int s = 0; s < kMaxSeg; ++s) ktiles += (g.K[s] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
   if (g.splits > 1 && (int64_t)(d.kper / BK) * (g.splits - 1) >= ktiles) return hipErrorInvalidValue;   // an empty split
+  // Both operands strided in the reduction index (the weight-gradient products): their global rows are
+  // 512 contiguous bytes whatever the reduction width, so the ring variant's deeper prefetch is free
+  // (measured +7 %); with a reduction-contiguous operand its 64-byte row segments cost more than they hide.
+  if (big_tile && !g.a_kc && !g.b_kc && !d.drop_thr) return launch_ring_oriented<false, false>(g, d, st);
   return big_tile ? launch_tile<true>(g, d, st) : launch_tile<false>(g, d, st);
 }
 
