@@ -63,7 +63,7 @@ def _traffic_from_profiles(workload: str, stage: str):
         return None
 
 
-def cpu_baseline(inp, budget_s: float = 20.0):
+def cpu_baseline(inp, budget_s: float = 40.0):
     """Oracle fwd+bwd on the first sentences of the batch, about `budget_s` seconds."""
     from oracle import attn_softmax_oracle as orc
     try:
