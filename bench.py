@@ -6,15 +6,18 @@ attn_softmax_fwd and attn_softmax_bwd) over one batch of synthetic input that
 is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload stress|large|mid|small|tiny]
-                    [--dtype bf16|f32] [--no-cpu-baseline]
+                    [--dtype bf16|f32] [--no-cpu-baseline] [--all-rows]
 
 value      = non-pad target tokens per second, fwd+bwd, whole job (one GPU)
-roofline   = the kernel that takes the most time (a vocabulary GEMM): algorithmic
-             flops 2*N*H*V per launch / its average launch duration, measured with
+rows       = R, the rows the vocabulary part of the path runs on: the non-pad target
+             positions (row compaction, as_shape.skip_pad_rows = 1, the default here), or
+             all N = T*B positions with --all-rows
+roofline   = the kernel that takes the most time (a vocabulary GEMM): the flops it
+             executes, 2*R*H*V per launch / its average launch duration, measured with
              HIP events on the launch stream inside the timed region, against the
              dense bf16 MFMA peak (2.5 PFLOP/s)
 roofline_hbm = the two streaming softmax-cross-entropy kernels against the 8 TB/s
-             HBM peak (algorithmic bytes N*V*e for the statistics pass, 2*N*V*e for
+             HBM peak (algorithmic bytes R*V*e for the statistics pass, 2*R*V*e for
              the in-place dlogits pass)
 cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
              sentences of the same workload (a reported baseline, not a target)
@@ -40,16 +43,16 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
-GEMM_STAGES = {  # stage -> algorithmic flops per launch as a function of the shape
-    "gemm_logits": lambda N, H, V, T, S, B: 2.0 * N * H * V,
-    "gemm_dwout": lambda N, H, V, T, S, B: 2.0 * N * H * V,
-    "gemm_dhc": lambda N, H, V, T, S, B: 2.0 * N * H * V,
-    "gemm_q": lambda N, H, V, T, S, B: 2.0 * N * H * H,
-    "gemm_hc": lambda N, H, V, T, S, B: 4.0 * N * H * H,
-    "gemm_dwc": lambda N, H, V, T, S, B: 2.0 * N * H * H,      # per launch (two launches per step)
-    "gemm_dch": lambda N, H, V, T, S, B: 2.0 * N * H * H,      # per launch (two launches per step)
-    "gemm_dwa": lambda N, H, V, T, S, B: 2.0 * N * H * H,
-    "gemm_dh": lambda N, H, V, T, S, B: 2.0 * N * H * H,
+GEMM_STAGES = {  # stage -> flops per launch; N = all positions, R = rows of the vocabulary part
+    "gemm_logits": lambda N, R, H, V: 2.0 * R * H * V,
+    "gemm_dwout": lambda N, R, H, V: 2.0 * R * H * V,
+    "gemm_dhc": lambda N, R, H, V: 2.0 * R * H * V,
+    "gemm_q": lambda N, R, H, V: 2.0 * N * H * H,
+    "gemm_hc": lambda N, R, H, V: 4.0 * N * H * H,
+    "gemm_dwc": lambda N, R, H, V: 2.0 * N * H * H,      # per launch (two launches per step)
+    "gemm_dch": lambda N, R, H, V: 2.0 * N * H * H,      # per launch (two launches per step)
+    "gemm_dwa": lambda N, R, H, V: 2.0 * N * H * H,
+    "gemm_dh": lambda N, R, H, V: 2.0 * N * H * H,
 }
 
 
@@ -139,6 +142,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--train-step", action="store_true",
                     help="a step = fwd with dropout 0.3 + bwd + Adam update of W_a, W_c, W_out, b_out")
+    ap.add_argument("--all-rows", action="store_true",
+                    help="run the vocabulary part on all T*B positions (skip_pad_rows = 0) instead of the "
+                         "non-pad ones")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -170,11 +176,12 @@ def main():
     inp = make_inputs(a.workload, dtype=a.dtype)
     if a.train_step:
         inp.dropout_p, inp.dropout_seed = 0.3, 20190900562
-    db = lib.DeviceBatch(inp)
+    db = lib.DeviceBatch(inp, skip_pad_rows=not a.all_rows)
     T, S, B, H, V = inp.T, inp.S, inp.B, inp.H, inp.V
     N = T * B
     e = 2 if inp.dtype == "bf16" else 4
     n_tok = inp.n_nonpad()
+    R = N if a.all_rows else n_tok                       # rows of the vocabulary part
 
     # Adam state of the four parameter tensors: float master copy and both moments
     params = [("W_a", "dW_a"), ("W_c", "dW_c"), ("W_out", "dW_out"), ("b_out", "db_out")]
@@ -235,7 +242,7 @@ def main():
     if not a.no_stage_events:
         gemm_ms = {k: step_ms_by_stage.get(k, 0.0) for k in GEMM_STAGES}
         dom = max(gemm_ms, key=gemm_ms.get)
-        flops = GEMM_STAGES[dom](N, H, V, T, S, B)
+        flops = GEMM_STAGES[dom](N, R, H, V)
         avg_ms = per_stage[dom]
         ach = flops / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
         bf = inp.dtype == "bf16"
@@ -246,8 +253,8 @@ def main():
         # all three vocabulary GEMMs together (they are >90 % of the path's flops)
         voc_ms = sum(step_ms_by_stage.get(k, 0.0) for k in ("gemm_logits", "gemm_dwout", "gemm_dhc"))
         if voc_ms > 0:
-            roofline["vocab_gemms_tflops"] = 6.0 * N * H * V / (voc_ms * 1e-3) / 1e12
-        sb = float(N) * V * e
+            roofline["vocab_gemms_tflops"] = 6.0 * R * H * V / (voc_ms * 1e-3) / 1e12
+        sb = float(R) * V * e
         st_ms, dl_ms = per_stage.get("xent_stats", 0.0), per_stage.get("xent_dlogits", 0.0)
         tot = st_ms + dl_ms
         if tot > 0:
@@ -268,9 +275,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": inp.dtype, "data": "synthetic",
         "config": {"workload": a.workload, "B": B, "T": T, "S": S, "H": H, "V": V, "positions": N,
-                   "non_pad_tokens": n_tok, "grad_scale": inp.grad_scale},
+                   "non_pad_tokens": n_tok, "grad_scale": inp.grad_scale,
+                   "skip_pad_rows": 0 if a.all_rows else 1, "rows_in_vocabulary_part": R},
         "positions_per_sec": N / (dt / a.steps),
-        "path_tflops": (6.0 * N * H * V + 18.0 * N * H * H + 12.0 * B * T * S * H) / (dt / a.steps) / 1e12,
+        "path_tflops": (6.0 * R * H * V + 18.0 * N * H * H + 12.0 * B * T * S * H) / (dt / a.steps) / 1e12,
         "roofline": roofline,
         "roofline_hbm": roofline_hbm,
         "stage_ms_per_step": {k: round(v, 5) for k, v in step_ms_by_stage.items()},

@@ -77,6 +77,16 @@ typedef struct {
    * 0 switches it off.  The caller changes dropout_seed from step to step. */
   float dropout_p;
   uint64_t dropout_seed;
+  /* Row compaction, 0 or 1.  A position whose target is padding contributes nothing to
+   * the loss or to any gradient (Eq. 6 sums over the words of the sentence), so with 1
+   * the vocabulary part of the path -- logits, softmax cross-entropy, dW_out, the
+   * product with W_out in the backward pass -- runs only on the rows whose target is a
+   * word.  The row list is made on the device; nothing is synchronised.  Loss, n_tok,
+   * masks and all six gradients are the same as with 0 (up to the order of fp32
+   * sums); at padding positions tok_loss = 0 and argmax = pad_id, and AS_VIEW_LOGITS /
+   * AS_VIEW_LSE hold one row per non-pad position, in increasing n, located through
+   * AS_VIEW_ROW_POS.  The per-step entry points ignore it. */
+  int32_t skip_pad_rows;
 } as_shape;
 
 /* Saved activations readable through attn_softmax_view(). */
@@ -86,7 +96,9 @@ typedef enum {
   AS_VIEW_HC = 2,      /* dtype  [T,B,H]   tanh(W_c[c;h]) (Eq. 4)                   */
   AS_VIEW_LOGITS = 3,  /* dtype  [N,ld]    logits after fwd, dlogits after bwd;     */
                        /*                  ld = *row_stride elements (>= V)         */
-  AS_VIEW_LSE = 4      /* float  [T,B]     log-sum-exp of each logits row           */
+  AS_VIEW_LSE = 4,     /* float  [T,B]     log-sum-exp of each logits row           */
+  AS_VIEW_ROW_POS = 5  /* int32  [T,B]     skip_pad_rows = 1 only: row of position (t,b) in */
+                       /*                  AS_VIEW_LOGITS / AS_VIEW_LSE, -1 at padding      */
 } as_view;
 
 /* Bytes of workspace fwd+bwd need for this shape; 0 if the shape is invalid. */
@@ -171,7 +183,8 @@ typedef enum {
   AS_STAGE_GEMM_DH = 15,      /* d_h_dec = dH1 + dQ W_a^T                    */
   AS_STAGE_MISC = 16,         /* small reductions, split-K combine           */
   AS_STAGE_ADAM = 17,         /* attn_softmax_adam_step                      */
-  AS_STAGE_COUNT = 18
+  AS_STAGE_COMPACT = 18,      /* row list, gather of h_c rows, scatter of dz */
+  AS_STAGE_COUNT = 19
 } as_stage;
 
 as_status attn_softmax_profile_enable(int enable);

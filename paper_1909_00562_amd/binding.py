@@ -17,12 +17,12 @@ _LIB_PATH = os.path.join(_PKG, "libattn_softmax.so")
 _lib = None
 
 AS_F32, AS_BF16 = 0, 1
-AS_VIEW_ALPHA, AS_VIEW_CTX, AS_VIEW_HC, AS_VIEW_LOGITS, AS_VIEW_LSE = range(5)
+AS_VIEW_ALPHA, AS_VIEW_CTX, AS_VIEW_HC, AS_VIEW_LOGITS, AS_VIEW_LSE, AS_VIEW_ROW_POS = range(6)
 STATUS_NAMES = {0: "AS_OK", 1: "AS_ERR_NULL", 2: "AS_ERR_SHAPE", 3: "AS_ERR_DTYPE",
                 4: "AS_ERR_WORKSPACE", 5: "AS_ERR_ALIGN", 6: "AS_ERR_HIP"}
 STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "gemm_logits",
                "xent_stats", "xent_dlogits", "gemm_dwout", "gemm_dhc", "gemm_dwc", "gemm_dch",
-               "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam"]
+               "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam", "compact"]
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
            "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
@@ -39,7 +39,8 @@ class AsShape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("S", ctypes.c_int32), ("B", ctypes.c_int32),
                 ("H", ctypes.c_int32), ("V", ctypes.c_int32), ("pad_id", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("grad_scale", ctypes.c_float),
-                ("dropout_p", ctypes.c_float), ("dropout_seed", ctypes.c_uint64)]
+                ("dropout_p", ctypes.c_float), ("dropout_seed", ctypes.c_uint64),
+                ("skip_pad_rows", ctypes.c_int32)]
 
 
 class AsAdam(ctypes.Structure):
@@ -190,7 +191,7 @@ class DeviceBatch:
     """Device buffers for one batch: uploads the inputs, owns outputs and the
     workspace, and forwards to the C ABI.  No arithmetic happens here."""
 
-    def __init__(self, inp, device="cuda:0"):
+    def __init__(self, inp, device="cuda:0", skip_pad_rows=False):
         import torch
         self.torch = torch
         self.inp = inp
@@ -198,7 +199,7 @@ class DeviceBatch:
         bf = inp.dtype == "bf16"
         self.shape = AsShape(inp.T, inp.S, inp.B, inp.H, inp.V, inp.pad_id, AS_BF16 if bf else AS_F32,
                              float(inp.grad_scale), float(getattr(inp, "dropout_p", 0.0)),
-                             int(getattr(inp, "dropout_seed", 0)))
+                             int(getattr(inp, "dropout_seed", 0)), 1 if skip_pad_rows else 0)
         tdt = torch.bfloat16 if bf else torch.float32
         self.tdt = tdt
 
@@ -242,7 +243,8 @@ class DeviceBatch:
                          self.dW_a, self.dW_c, self.dW_out, self.db_out, self._stream())
 
     def view(self, which: int):
-        """Saved activation as a torch tensor aliasing the workspace."""
+        """Saved activation as a torch tensor aliasing the workspace.  With skip_pad_rows the logits and lse
+        views are [N, V] / [N] with one row per non-pad position (AS_VIEW_ROW_POS maps (t, b) to its row)."""
         torch = self.torch
         addr, nbytes, ld = attn_softmax_view(self.shape, self.workspace, which)
         off = addr - self.workspace.data_ptr()
@@ -250,11 +252,16 @@ class DeviceBatch:
         T, S, B, H, V = self.inp.T, self.inp.S, self.inp.B, self.inp.H, self.inp.V
         if which == AS_VIEW_ALPHA:
             return raw.view(torch.float32).view(B, T, S)
+        compact = self.shape.skip_pad_rows != 0
+        if which == AS_VIEW_ROW_POS:
+            return raw.view(torch.int32).view(T, B)
         if which == AS_VIEW_LSE:
-            return raw.view(torch.float32).view(T, B)
+            return raw.view(torch.float32).view(T * B) if compact else raw.view(torch.float32).view(T, B)
         if which in (AS_VIEW_CTX, AS_VIEW_HC):
             return raw.view(self.tdt).view(T, B, H)
         if which == AS_VIEW_LOGITS:
+            if compact:
+                return raw.view(self.tdt).view(T * B, ld)[:, :V]
             return raw.view(self.tdt).view(T, B, ld)[:, :, :V]
         raise ValueError(which)
 

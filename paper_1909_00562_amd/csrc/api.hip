@@ -82,6 +82,10 @@ struct Layout {
   // rounding remainders (value - stored(value)) of operands made inside the attention core,
   // and the tanh derivative 1 - h_c^2 taken before h_c is rounded
   size_t q_lo, alphaE_lo, dC_lo, dscoreE_lo, dact, dz_lo, ctx_lo;
+  // row compaction (skip_pad_rows): position <-> compacted row, the count, and the gathered / to-be-scattered blocks
+  bool compact;
+  bool dhc_dyn;   // the product with W_out in the backward pass picks its reduction split on the device
+  size_t row_pos, rows, n_act, hc_c, dact_c, dz_c, dz_lo_c;
   int rb, nrb;
   GemmPlan p_q, p_score, p_ctx, p_hc, p_logits, p_dwout, p_dhc, p_dwc, p_dch, p_dalpha, p_dq, p_ds, p_dwa, p_dh;
   size_t partial_bytes;
@@ -92,6 +96,7 @@ bool shape_ok(const as_shape* s) {
   if (s->T < 1 || s->S < 1 || s->B < 1 || s->H < 1 || s->V < 1) return false;
   if (s->pad_id < 0 || s->pad_id >= s->V) return false;
   if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return false;
+  if (s->skip_pad_rows != 0 && s->skip_pad_rows != 1) return false;
   if (s->dtype != AS_F32 && s->dtype != AS_BF16) return false;
   const int64_t N = (int64_t)s->T * s->B;
   if (N > (1 << 30) || (int64_t)s->S * s->B > (1 << 30)) return false;
@@ -118,6 +123,10 @@ Layout make_layout(const as_shape* s) {
   L.p_logits = gemm_plan(N, V, H, 1, bf, false);
   L.p_dwout = gemm_plan(V, H, N, 1, bf, true);
   L.p_dhc = gemm_plan(N, H, V, 1, bf, true);
+  // Few, long work items (N/256 x H/256 tiles, reduction over V): once the padding rows are gone the item count
+  // no longer fills whole rounds of the grid, so the kernel splits the reduction to fit the count it reads.
+  L.dhc_dyn = s->skip_pad_rows != 0 && bf && L.p_dhc.big_tile;
+  if (L.dhc_dyn && L.p_dhc.splits < 8) L.p_dhc.splits = 8;
   L.p_dwc = gemm_plan(H, H, N, 1, bf, true);
   L.p_dch = gemm_plan(N, H, H, 1, bf, false);
   L.p_dalpha = gemm_plan(T, S, H, B, bf, false);
@@ -165,6 +174,17 @@ Layout make_layout(const as_shape* s) {
   L.dact = take(NH * 4);
   L.ctx_lo = take(NH * L.e);
   L.dz_lo = take(NH * L.e);
+  L.compact = s->skip_pad_rows != 0;
+  L.row_pos = L.rows = L.n_act = L.hc_c = L.dact_c = L.dz_c = L.dz_lo_c = 0;
+  if (L.compact) {
+    L.row_pos = take((size_t)N * 4);
+    L.rows = take((size_t)N * 4);
+    L.n_act = take(16);
+    L.hc_c = take(NH * L.e);
+    L.dact_c = take(NH * 4);
+    L.dz_c = take(NH * L.e);
+    L.dz_lo_c = take(NH * L.e);
+  }
   L.total = off;
   return L;
 }
@@ -177,8 +197,8 @@ as_status check_common(const as_shape* s, const void* h_dec, const void* h_enc, 
   if (!s) return fail(AS_ERR_NULL, "shape is NULL");
   if (s->dtype != AS_F32 && s->dtype != AS_BF16) return fail(AS_ERR_DTYPE, "unknown dtype %d", s->dtype);
   if (!shape_ok(s))
-    return fail(AS_ERR_SHAPE, "bad shape T=%d S=%d B=%d H=%d V=%d pad_id=%d dropout_p=%g", s->T, s->S, s->B, s->H,
-                s->V, s->pad_id, (double)s->dropout_p);
+    return fail(AS_ERR_SHAPE, "bad shape T=%d S=%d B=%d H=%d V=%d pad_id=%d dropout_p=%g skip_pad_rows=%d", s->T, s->S,
+                s->B, s->H, s->V, s->pad_id, (double)s->dropout_p, s->skip_pad_rows);
   if (!h_dec || !h_enc || !src_len || !W_a || !W_c || !W_out || !b_out || !targets || !ws)
     return fail(AS_ERR_NULL, "a required pointer is NULL");
   if (s->dtype == AS_BF16 && (s->H % 8) != 0) return fail(AS_ERR_ALIGN, "AS_BF16 needs H %% 8 == 0 (H=%d)", s->H);
@@ -226,19 +246,34 @@ static as_status fwd_from_ctx(const as_shape* s, const Layout& L, char* w, const
     }
     AS_TRY(AS_STAGE_GEMM_HC, launch_gemm(g, bf, L.p_hc.big_tile, st));
   }
+  // Padding rows drop out of Eq. 5-6 here: the rows of h_c (and of its saved derivative) whose target is a
+  // word are gathered into a dense block, and everything over the vocabulary runs on that block alone.
+  const int32_t* rows = nullptr;
+  const int32_t* n_act = nullptr;
+  if (L.compact) {
+    rows = reinterpret_cast<const int32_t*>(w + L.rows);
+    n_act = reinterpret_cast<const int32_t*>(w + L.n_act);
+    AS_TRY(AS_STAGE_COMPACT, launch_row_compact(targets, N, V, s->pad_id, reinterpret_cast<int32_t*>(w + L.row_pos),
+                                                reinterpret_cast<int32_t*>(w + L.rows),
+                                                reinterpret_cast<int32_t*>(w + L.n_act), tgt_mask, tok_loss, argmax, st));
+    AS_TRY(AS_STAGE_COMPACT, launch_gather_rows(rows, n_act, N, w + L.hc, w + L.hc_c, (int64_t)H * L.e, w + L.dact,
+                                                w + L.dact_c, (int64_t)H * 4, st));
+  }
   {  // logits = h_c W_out^T + b_out                                        (Eq. 5)
     GemmArgs g;
-    g.seg(w + L.hc, H, 0, W_out, H, 0, H);
+    g.seg(L.compact ? w + L.hc_c : w + L.hc, H, 0, W_out, H, 0, H);
     g.a_kc = true; g.b_kc = true;
     g.M = N; g.N = V; g.bias = b_out;
+    g.M_dev = n_act;
     g.C = w + L.logits; g.ldc = L.ldV; g.c_bf16 = bf;
     AS_TRY(AS_STAGE_GEMM_LOGITS, launch_gemm(g, bf, L.p_logits.big_tile, st));
   }
   AS_TRY(AS_STAGE_XENT_STATS,                                          // Eq. 5-6
          launch_xent_stats(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id, reinterpret_cast<float*>(w + L.lse),
-                           reinterpret_cast<float*>(w + L.tokloss), tok_loss, argmax, tgt_mask, st));
+                           reinterpret_cast<float*>(w + L.tokloss), tok_loss, argmax, L.compact ? nullptr : tgt_mask,
+                           rows, n_act, st));
   AS_TRY(AS_STAGE_MISC, launch_loss_reduce(reinterpret_cast<const float*>(w + L.tokloss), targets, N, V, s->pad_id,
-                                           loss_sum, n_tok, st));
+                                           loss_sum, n_tok, n_act, st));
   return AS_OK;
 }
 
@@ -268,6 +303,9 @@ as_status attn_softmax_view(const as_shape* shape, void* workspace, int which, v
     case AS_VIEW_HC: *ptr = w + L.hc; *bytes = NH * L.e; ld = shape->H; break;
     case AS_VIEW_LOGITS: *ptr = w + L.logits; *bytes = (size_t)L.N * L.ldV * L.e; ld = L.ldV; break;
     case AS_VIEW_LSE: *ptr = w + L.lse; *bytes = (size_t)L.N * 4; ld = shape->B; break;
+    case AS_VIEW_ROW_POS:
+      if (!L.compact) return fail(AS_ERR_SHAPE, "AS_VIEW_ROW_POS exists only with skip_pad_rows = 1");
+      *ptr = w + L.row_pos; *bytes = (size_t)L.N * 4; ld = shape->B; break;
     default: return fail(AS_ERR_SHAPE, "unknown view %d", which);
   }
   if (row_stride) *row_stride = ld;
@@ -353,16 +391,19 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
   float* partial = reinterpret_cast<float*>(w + L.partial);
 
   // dlogits = g (softmax - onehot) in place; db_out = column sums
+  const int32_t* rows = L.compact ? reinterpret_cast<const int32_t*>(w + L.rows) : nullptr;
+  const int32_t* n_act = L.compact ? reinterpret_cast<const int32_t*>(w + L.n_act) : nullptr;
   AS_TRY(AS_STAGE_XENT_DLOGITS,
          launch_xent_dlogits(w + L.logits, L.ldV, bf, N, V, targets, s->pad_id,
                              reinterpret_cast<const float*>(w + L.lse), s->grad_scale,
-                             reinterpret_cast<float*>(w + L.dbpart), st));
+                             reinterpret_cast<float*>(w + L.dbpart), rows, n_act, st));
   AS_TRY(AS_STAGE_MISC, launch_db_reduce(reinterpret_cast<const float*>(w + L.dbpart), L.nrb, V, db_out, st));
   {  // dW_out = dlogits^T h_c
     GemmArgs g;
-    g.seg(w + L.logits, L.ldV, 0, w + L.hc, H, 0, N);
+    g.seg(w + L.logits, L.ldV, 0, L.compact ? w + L.hc_c : w + L.hc, H, 0, N);
     g.a_kc = false; g.b_kc = false;
     g.M = V; g.N = H;
+    g.K_dev = n_act;     // compacted: the reduction runs over the non-pad rows only
     g.C = dW_out; g.ldc = H; g.c_bf16 = false;
     g.splits = L.p_dwout.splits; g.partial = partial;
     AS_TRY(AS_STAGE_GEMM_DWOUT, launch_gemm(g, bf, L.p_dwout.big_tile, st));
@@ -372,12 +413,17 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
     g.seg(w + L.logits, L.ldV, 0, W_out, H, 0, V);
     g.a_kc = true; g.b_kc = false;
     g.M = N; g.N = H;
-    g.gate = reinterpret_cast<const float*>(w + L.dact); g.ldg = H;
-    g.C = w + L.dz; g.ldc = H; g.c_bf16 = bf;
-    g.C_lo = w + L.dz_lo;
+    g.gate = reinterpret_cast<const float*>(w + (L.compact ? L.dact_c : L.dact)); g.ldg = H;
+    g.C = w + (L.compact ? L.dz_c : L.dz); g.ldc = H; g.c_bf16 = bf;
+    g.C_lo = w + (L.compact ? L.dz_lo_c : L.dz_lo);
+    g.M_dev = n_act;
+    g.dyn_split = L.dhc_dyn;
     g.splits = L.p_dhc.splits; g.partial = partial;
     AS_TRY(AS_STAGE_GEMM_DHC, launch_gemm(g, bf, L.p_dhc.big_tile, st));
   }
+  if (L.compact)   // dz back to its time-major rows, zeros at the padding rows: the rest of the pass is per sentence
+    AS_TRY(AS_STAGE_COMPACT, launch_scatter_rows(reinterpret_cast<const int32_t*>(w + L.row_pos), N, w + L.dz_c,
+                                                 w + L.dz, w + L.dz_lo_c, w + L.dz_lo, (int64_t)H * L.e, st));
   for (int half = 0; half < 2; ++half) {  // dW_c = dz^T [ctx ; h_dec]
     GemmArgs g;
     g.seg(w + L.dz, H, 0, half == 0 ? (const void*)(w + L.ctx) : (const void*)hd, H, 0, N);
@@ -484,6 +530,7 @@ bool step_shape_ok(const as_shape* s, as_shape* s1) {
   if (!s) return false;
   *s1 = *s;
   s1->T = 1;
+  s1->skip_pad_rows = 0;   // a step is also asked for predictions at padding targets: every row is computed
   return shape_ok(s1) && !(s->dtype == AS_BF16 && (s->H % 8) != 0);
 }
 }  // namespace

@@ -62,7 +62,42 @@ struct GemmArgs {
   int batch = 1;
   int splits = 1;               // split of the reduction index (single segment only)
   float* partial = nullptr;     // [batch*splits, M, N] floats when splits > 1
+  // Sizes known only on the device (a row count made by an earlier kernel of the same stream).  M and K[0]
+  // stay the upper bounds every grid, plan and buffer is sized for; a kernel reads the count once and
+  // uses min(count, bound) in their place: rows >= *M_dev of A are not read and of C not written, reduction
+  // indices >= *K_dev of segment 0 are not read (so neither operand has to be defined there).
+  const int32_t* M_dev = nullptr;   // batch == 1 only
+  const int32_t* K_dev = nullptr;   // single segment only
+  // With M_dev, the 256x256 persistent kernel and a product of few, long work items (fewer output tiles than a
+  // few rounds of the grid): `splits` (>= 2) is then only the bound `partial` is sized for; the kernel picks the
+  // split of the reduction from the row count it reads (pp_dyn_splits below), so that the shrunken work list
+  // still fills whole rounds of the grid, and the combine step, which always runs, picks the same.
+  bool dyn_split = false;
 };
+
+// Blocks of a persistent launch (one per compute unit, a multiple of the 8 XCDs).
+inline int pp_grid_blocks(int work_total) { return work_total < 256 ? (work_total + 7) / 8 * 8 : 256; }
+
+// Reduction split for `tiles` output tiles of `ktiles` reduction tiles each on `blocks` persistent blocks.  Cost in
+// sixteenths of one reduction tile of one block: rounds of the grid times (the split's tiles + 6 for an item's
+// prologue and epilogue), plus the round trip of each split's fp32 partial through HBM (256x256x8 bytes per
+// tile, spread over the chip: about 7/6 sixteenths per tile and split).  Integer arithmetic: the product
+// kernel and the combine kernel must arrive at the same number.
+__host__ __device__ inline int pp_dyn_splits(int tiles, int ktiles, int smax, int blocks) {
+  int best = 1;
+  long long best_cost = -1;
+  for (int s = 1; s <= smax; ++s) {
+    const int per = (ktiles + s - 1) / s;
+    if (s > 1 && (long long)per * (s - 1) >= ktiles) continue;   // a split would be empty
+    const long long rounds = ((long long)tiles * s + blocks - 1) / blocks;
+    const long long cost = rounds * (per + 6) * 16 + (long long)s * tiles * 7 / 6;
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = s;
+    }
+  }
+  return best;
+}
 
 // Tile plan shared by workspace sizing and launching.
 struct GemmPlan {

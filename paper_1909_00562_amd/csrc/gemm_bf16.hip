@@ -51,7 +51,18 @@ struct GemmDev {
   int group;   // tile rows per group of the persistent kernel's tile walk
   int kper;    // reduction elements per split, multiple of 64
   int vec_ok;  // rows of C (and C_lo, C_dact, gate) allow 8/16-byte vector access
+  const int32_t* M_dev;   // device-side row count (or null): min(*M_dev, M) rows are valid
+  const int32_t* K_dev;   // device-side reduction length of segment 0 (or null)
+  int nz;                 // batch * splits
+  int dyn_split;          // splits is the bound of a split chosen in the kernel from the row count (pp kernel)
 };
+
+// size made by an earlier kernel of the stream, clamped to the bound the launch was sized for
+__device__ __forceinline__ int dev_bound(const int32_t* count, int bound) {
+  if (!count) return bound;
+  const int v = *count;
+  return v < 0 ? 0 : (v < bound ? v : bound);
+}
 
 constexpr int BK = 64;                  // reduction elements per LDS tile row
 constexpr int ROWB = BK * 2;            // bytes per LDS tile row
@@ -156,8 +167,9 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 // the row part of an address is a scalar offset, the lane part one register, and rows
 // beyond M are dropped by pointing the lane offset outside the resource instead of branching.
 template <int TM, int TN, bool OUT_BF16, bool DROP, int CH, int EP_LD>
-__device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
-                                                  int lane, int row0, int col0, int batch, int z) {
+__device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x16_t (&acc)[TM][TN],
+                                                  unsigned char* region, int lane, int row0, int col0, int batch,
+                                                  int z) {
   constexpr int WAIT_LGKM_ONLY = 0xC07F;
   constexpr int ES = OUT_BF16 ? 2 : 4;
   float* stage_f = reinterpret_cast<float*>(region);
@@ -172,7 +184,7 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
   const __amdgpu_buffer_rsrc_t rs_lo = make_rsrc(p.C_lo ? p.C_lo + origin : nullptr);
   const __amdgpu_buffer_rsrc_t rs_da = make_rsrc(p.C_dact ? p.C_dact + origin : nullptr);
   const float* gate0 = p.gate ? p.gate + (int64_t)row0 * p.ldg + col0 : nullptr;   // gate and old-C reads: plain loads
-  const int rows_left = p.M - row0 - vrow;                       // rows of C from this lane's first row on
+  const int rows_left = Mv - row0 - vrow;                        // valid rows of C from this lane's first row on
   const bool col_in = col0 + vcol < p.N;                         // N % 4 == 0: a 4-column group is all in or all out
   const uint32_t lane_off = (uint32_t)(vrow * ld + vcol);        // elements, inside the wave tile's window
   const uint32_t lane_off_g = (uint32_t)(vrow * p.ldg + vcol);
@@ -259,12 +271,12 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, f32x16_t (&a
 }
 
 template <int TM, int TN, bool OUT_BF16, bool VEC, bool DROP, int CH = 32, int EP_LD = 72>
-__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[TM][TN], unsigned char* region,
-                                              int lane, int row0, int col0, int batch, int z) {
+__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, int Mv, f32x16_t (&acc)[TM][TN],
+                                              unsigned char* region, int lane, int row0, int col0, int batch, int z) {
   static_assert(TN == 2, "64-column wave tiles");
   static_assert(CH == 32 || CH == 16, "chunk of one or half an MFMA tile");
   if constexpr (VEC) {
-    gemm_epilogue_vec<TM, TN, OUT_BF16, DROP, CH, EP_LD>(p, acc, region, lane, row0, col0, batch, z);
+    gemm_epilogue_vec<TM, TN, OUT_BF16, DROP, CH, EP_LD>(p, Mv, acc, region, lane, row0, col0, batch, z);
     return;
   }
   constexpr int WAIT_LGKM_ONLY = 0xC07F;   // leaves global loads in flight
@@ -295,7 +307,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, f32x16_t (&acc)[
     for (int it = 0; it < CH / 4; ++it) {
       const int lr = it * 4 + vrow;
       const int grow = row0 + i * 32 + part * CH + lr;
-      if (grow >= p.M || gcol >= p.N) continue;
+      if (grow >= Mv || gcol >= p.N) continue;
       const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
       float v[4] = {v4[0], v4[1], v4[2], v4[3]};
       if (Pz) {
@@ -413,6 +425,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   const int in_g = pid - gid * gsize;
   const int tile_m = first_m + in_g % gm, tile_n = in_g / gm;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int Mv = dev_bound(p.M_dev, p.M);   // valid rows: the grid was sized for p.M
+  const int K0 = dev_bound(p.K_dev, p.K[0]);
+  if (m0 >= Mv) return;                     // the whole block, before any barrier
 
   const int z = blockIdx.z;
   const int batch = z / p.splits, split = z - batch * p.splits;
@@ -423,12 +438,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   int nk = 0;
 #pragma unroll
   for (int s = 0; s < kMaxSeg; ++s) {
-    nks[s] = (p.K[s] + BK - 1) / BK;
+    nks[s] = ((s == 0 ? K0 : p.K[s]) + BK - 1) / BK;
     nk += nks[s];
   }
   int seg0 = 0, skip0 = 0;   // first segment of this block and reduction tiles skipped inside it
   if (p.splits > 1) {
-    const int tper = p.kper / BK;
+    // a reduction length read on the device is split here (a split may then come out empty: it stores zeros)
+    const int tper = p.K_dev ? (nk + p.splits - 1) / p.splits : p.kper / BK;
     const int t0 = split * tper;
     const int t1 = t0 + tper < nk ? t0 + tper : nk;
     nk = t1 > t0 ? t1 - t0 : 0;
@@ -453,7 +469,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   DirectLoader<BN, NW> dlb;
   TransposeLoader<BM, NT> tla;
   TransposeLoader<BN, NT> tlb;
-  if constexpr (AKC) dla.init(p.lda[0], p.M - m0, wave, lane); else tla.init(p.lda[0], p.M - m0, tid);
+  if constexpr (AKC) dla.init(p.lda[0], Mv - m0, wave, lane); else tla.init(p.lda[0], Mv - m0, tid);
   if constexpr (BKC) dlb.init(p.ldb[0], p.N - n0, wave, lane); else tlb.init(p.ldb[0], p.N - n0, tid);
   constexpr int NLA = AKC ? DirectLoader<BM, NW>::NL : TransposeLoader<BM, NT>::NL;
   constexpr int NLB = BKC ? DirectLoader<BN, NW>::NL : TransposeLoader<BN, NT>::NL;
@@ -462,7 +478,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   // cursor over the reduction tiles of all segments: operand pointers of the next tile to load
   const int64_t stepA = AKC ? BK : (int64_t)BK * p.lda[0], stepB = BKC ? BK : (int64_t)BK * p.ldb[0];
   const int64_t offA = AKC ? (int64_t)m0 * p.lda[0] : m0, offB = BKC ? (int64_t)n0 * p.ldb[0] : n0;
-  int cseg = seg0, ck_left = p.K[seg0] - kbeg0;
+  int cseg = seg0, ck_left = (seg0 == 0 ? K0 : p.K[seg0]) - kbeg0;
   const uint16_t* cA = p.A[seg0] + (int64_t)batch * p.sA[seg0] + offA + (AKC ? kbeg0 : (int64_t)kbeg0 * p.lda[0]);
   const uint16_t* cB = p.B[seg0] + (int64_t)batch * p.sB[seg0] + offB + (BKC ? kbeg0 : (int64_t)kbeg0 * p.ldb[0]);
   auto advance = [&]() {
@@ -551,7 +567,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(GemmDev p) {
   }
   // (the last barrier above came after every wave's final fragment reads: LDS is free for the epilogue)
 
-  gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP>(p, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch, z);
+  gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP>(p, Mv, acc, smem + wave * 16384, lane, m0 + wm * WM, n0 + wn * WN, batch,
+                                             z);
 }
 
 
@@ -679,7 +696,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
   // blocks go round-robin to the 8 XCDs, so XCD x owns a contiguous run of items and
   // its blocks take them interleaved: co-resident blocks work on neighbouring tiles and
   // share operand panels in their XCD's L2.
-  const int nt = p.tiles_m * p.tiles_n;
+  // Sizes read on the device shrink the work list: the grid and work_total were sized for p.M.
+  const int Mv = dev_bound(p.M_dev, p.M);
+  const int K0 = dev_bound(p.K_dev, p.K[0]);
+  const int tiles_m = p.M_dev ? (Mv + BM - 1) / BM : p.tiles_m;
+  const int splits = p.dyn_split ? pp_dyn_splits(tiles_m * p.tiles_n, (K0 + BK - 1) / BK, p.splits, gridDim.x) : p.splits;
+  if (p.M_dev) work_total = tiles_m * p.tiles_n * (p.dyn_split ? splits : p.nz);
+  const int kper = (p.K_dev || p.dyn_split) ? (((K0 + BK - 1) / BK + splits - 1) / splits) * BK : p.kper;
+  const int nt = tiles_m * p.tiles_n;
   const int xcd = blockIdx.x & 7, bidx = blockIdx.x >> 3, nbx = gridDim.x >> 3;
   const int wper = work_total >> 3, wrem = work_total & 7;
   const int wbeg = xcd * wper + (xcd < wrem ? xcd : wrem);
@@ -696,17 +720,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
     const int gsize = GROUP * p.tiles_n;
     const int gid = pid / gsize;
     const int first_m = gid * GROUP;
-    const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
+    const int gm = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
     const int in_g = pid - gid * gsize;
     it.m0 = (first_m + in_g % gm) * BM;
     it.n0 = (in_g / gm) * BN;
-    it.batch = it.z / p.splits;
-    const int split = it.z - it.batch * p.splits;
+    it.batch = it.z / splits;
+    const int split = it.z - it.batch * splits;
     it.kbeg = 0;
-    it.kend = p.K[0];
-    if (p.splits > 1) {
-      it.kbeg = split * p.kper;
-      it.kend = it.kbeg + p.kper < p.K[0] ? it.kbeg + p.kper : p.K[0];
+    it.kend = K0;
+    if (splits > 1) {
+      it.kbeg = split * kper;
+      it.kend = it.kbeg + kper < K0 ? it.kbeg + kper : K0;
     }
     return it;
   };
@@ -737,7 +761,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
   int lbatch = 0;
   auto enter_item = [&]() {    // cursor to the first reduction tile of item lw
     const Item it = get_item(lw);
-    la.init(p.lda[0], p.M - it.m0, wave, lane);
+    la.init(p.lda[0], Mv - it.m0, wave, lane);
     lb.init(p.ldb[0], p.N - it.n0, wave, lane);
     offA = AKC ? (int64_t)it.m0 * p.lda[0] : it.m0;
     offB = BKC ? (int64_t)it.n0 * p.ldb[0] : it.n0;
@@ -820,7 +844,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
   int g = 0;                                        // reduction tiles done: stage parity
   for (int cw = wbeg + bidx; cw < wend; cw += nbx) {
     const Item it = get_item(cw);
-    const int nk = (it.kend - it.kbeg + BK - 1) / BK + nk_rest;
+    const int nk0 = (it.kend - it.kbeg + BK - 1) / BK;
+    const int nk = (nk0 > 0 ? nk0 : 1) + nk_rest;   // an empty reduction range is one tile of zeros, as the cursor issues it
     for (int t = 0; t < nk; ++t, ++g) {
       const int cur = g & 1, nxt = cur ^ 1;
       read_pair(cur, 0);                            // M0
@@ -838,8 +863,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
       }
     }
     // item done: write it out while the next item's first tile is already in flight
-    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, acc, smem + PP_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
-                                            it.n0 + wn * WN, it.batch, it.z);
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, Mv, acc, smem + PP_EPI_OFF + wave * 4096, lane,
+                                                       it.m0 + wm * WM, it.n0 + wn * WN, it.batch, it.z);
     zero_acc();
   }
 }
@@ -916,7 +941,13 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work
   // blocks go round-robin to the 8 XCDs, so XCD x owns a contiguous run of items and
   // its blocks take them interleaved: co-resident blocks work on neighbouring tiles and
   // share operand panels in their XCD's L2.
-  const int nt = p.tiles_m * p.tiles_n;
+  // Sizes read on the device shrink the work list: the grid and work_total were sized for p.M.
+  const int Mv = dev_bound(p.M_dev, p.M);
+  const int K0 = dev_bound(p.K_dev, p.K[0]);
+  const int tiles_m = p.M_dev ? (Mv + BM - 1) / BM : p.tiles_m;
+  if (p.M_dev) work_total = tiles_m * p.tiles_n * p.nz;
+  const int kper = p.K_dev ? (((K0 + BK - 1) / BK + p.splits - 1) / p.splits) * BK : p.kper;
+  const int nt = tiles_m * p.tiles_n;
   const int xcd = blockIdx.x & 7, bidx = blockIdx.x >> 3, nbx = gridDim.x >> 3;
   const int wper = work_total >> 3, wrem = work_total & 7;
   const int wbeg = xcd * wper + (xcd < wrem ? xcd : wrem);
@@ -933,17 +964,17 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work
     const int gsize = GROUP * p.tiles_n;
     const int gid = pid / gsize;
     const int first_m = gid * GROUP;
-    const int gm = (p.tiles_m - first_m) < GROUP ? (p.tiles_m - first_m) : GROUP;
+    const int gm = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
     const int in_g = pid - gid * gsize;
     it.m0 = (first_m + in_g % gm) * BM;
     it.n0 = (in_g / gm) * BN;
     it.batch = it.z / p.splits;
     const int split = it.z - it.batch * p.splits;
     it.kbeg = 0;
-    it.kend = p.K[0];
+    it.kend = K0;
     if (p.splits > 1) {
-      it.kbeg = split * p.kper;
-      it.kend = it.kbeg + p.kper < p.K[0] ? it.kbeg + p.kper : p.K[0];
+      it.kbeg = split * kper;
+      it.kend = it.kbeg + kper < K0 ? it.kbeg + kper : K0;
     }
     return it;
   };
@@ -974,7 +1005,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work
   int lbatch = 0;
   auto enter_item = [&]() {    // cursor to the first reduction tile of item lw
     const Item it = get_item(lw);
-    la.init(p.lda[0], p.M - it.m0, wave, lane);
+    la.init(p.lda[0], Mv - it.m0, wave, lane);
     lb.init(p.ldb[0], p.N - it.n0, wave, lane);
     offA = AKC ? (int64_t)it.m0 * p.lda[0] : it.m0;
     offB = BKC ? (int64_t)it.n0 * p.ldb[0] : it.n0;
@@ -1059,7 +1090,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work
   int g = 0;                                        // sub-tiles done: slot = g & 3
   for (int cw = wbeg + bidx; cw < wend; cw += nbx) {
     const Item it = get_item(cw);
-    const int nk = (it.kend - it.kbeg + RK - 1) / RK + nk_rest;
+    const int nk0 = (it.kend - it.kbeg + RK - 1) / RK;
+    const int nk = (nk0 > 0 ? nk0 : 1) + nk_rest;   // an empty reduction range is one sub-tile of zeros, as the cursor issues it
     for (int t = 0; t < nk; ++t, ++g) {
       const int slot = g & 3;
       read_pair(slot);                              // M
@@ -1076,8 +1108,8 @@ __global__ __launch_bounds__(512) void gemm_bf16_ring_kernel(GemmDev p, int work
       }
     }
     // item done: write it out while the next item's first sub-tiles are already in flight
-    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, acc, smem + RING_EPI_OFF + wave * 4096, lane, it.m0 + wm * WM,
-                                            it.n0 + wn * WN, it.batch, it.z);
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, Mv, acc, smem + RING_EPI_OFF + wave * 4096, lane,
+                                                       it.m0 + wm * WM, it.n0 + wn * WN, it.batch, it.z);
     zero_acc();
   }
 }
@@ -1094,7 +1126,7 @@ static hipError_t launch_ring(const GemmDev& d, int batch, hipStream_t st) {
     attr_set = true;
   }
   const int work_total = d.tiles_m * d.tiles_n * batch * d.splits;
-  int blocks = work_total < 256 ? (work_total + 7) / 8 * 8 : 256;
+  const int blocks = pp_grid_blocks(work_total);
   hipLaunchKernelGGL(kfn, dim3(blocks), dim3(512), smem, st, d, work_total);
   return hipGetLastError();
 }
@@ -1135,7 +1167,7 @@ static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
   }
   // persistent: one block per CU (a multiple of the 8 XCDs), each walking its share of the work items
   const int work_total = d.tiles_m * d.tiles_n * batch * d.splits;
-  int blocks = work_total < 256 ? (work_total + 7) / 8 * 8 : 256;
+  const int blocks = pp_grid_blocks(work_total);
   hipLaunchKernelGGL(kfn, dim3(blocks), dim3(512), smem, st, d, work_total);
   return hipGetLastError();
 }
@@ -1224,6 +1256,14 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   d.accumulate = g.accumulate;
   d.splits = g.splits;
   d.partial = g.partial;
+  if (g.M_dev && g.batch != 1) return hipErrorInvalidValue;
+  if (g.K_dev && g.K[1] != 0) return hipErrorInvalidValue;
+  d.M_dev = g.M_dev;
+  d.K_dev = g.K_dev;
+  d.nz = g.batch * g.splits;
+  // a split chosen in the kernel: persistent two-stage kernel, rows counted on the device, partial sums always
+  if (g.dyn_split && (!big_tile || !g.M_dev || g.splits < 2 || (!g.a_kc && !g.b_kc))) return hipErrorInvalidValue;
+  d.dyn_split = g.dyn_split ? 1 : 0;
   // vector epilogue: every row of C / C_lo / C_dact / gate starts 16-byte aligned
   // (ldc % 4 == 0 gives 8-byte alignment for bf16 rows, which their 8-byte stores need)
   d.vec_ok = ((g.ldc & 3) == 0) && ((g.sC & 3) == 0) && al16(g.C) && (!g.C_lo || al16(g.C_lo)) &&
@@ -1239,7 +1279,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, int big_tile, hipStream_t st) {
   int ktiles = 0;   // reduction tiles of all segments (the persistent kernel splits segment 0 alone, checked above)
   for (int s = 0; s < kMaxSeg; ++s) ktiles += (g.K[s] + BK - 1) / BK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * BK;
-  if (g.splits > 1 && (int64_t)(d.kper / BK) * (g.splits - 1) >= ktiles) return hipErrorInvalidValue;   // an empty split
+  if (g.splits > 1 && !g.dyn_split && (int64_t)(d.kper / BK) * (g.splits - 1) >= ktiles)
+    return hipErrorInvalidValue;   // an empty split
   // Both operands strided in the reduction index (the weight-gradient products): their global rows are
   // 512 contiguous bytes whatever the reduction width, so the ring variant's deeper prefetch is free
   // (measured +7 %); with a reduction-contiguous operand its 64-byte row segments cost more than they hide.

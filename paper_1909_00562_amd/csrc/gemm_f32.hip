@@ -28,7 +28,15 @@ struct GemmDevF {
   float* partial;
   int kper;
   int a_kc, b_kc;
+  const int32_t* M_dev;   // device-side row count / reduction length (or null), clamped to M / K[0]
+  const int32_t* K_dev;
 };
+
+__device__ __forceinline__ int dev_bound_f(const int32_t* count, int bound) {
+  if (!count) return bound;
+  const int v = *count;
+  return v < 0 ? 0 : (v < bound ? v : bound);
+}
 
 constexpr int FT = 64;   // block tile edge
 constexpr int FK = 16;   // reduction slice
@@ -39,6 +47,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;
   const int m0 = blockIdx.y * FT, n0 = blockIdx.x * FT;
+  const int Mv = dev_bound_f(p.M_dev, p.M);
+  const int K0 = dev_bound_f(p.K_dev, p.K[0]);
+  if (m0 >= Mv) return;   // the whole block, before any barrier
+  const int kper = p.K_dev ? (((K0 + FK - 1) / FK + p.splits - 1) / p.splits) * FK : p.kper;
   const int z = blockIdx.z;
   const int batch = z / p.splits, split = z - batch * p.splits;
 
@@ -50,10 +62,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
 
   for (int seg = 0; seg < kMaxSeg; ++seg) {
     if (p.K[seg] <= 0) continue;
-    int kbeg = 0, kend = p.K[seg];
+    int kbeg = 0, kend = seg == 0 ? K0 : p.K[seg];
     if (p.splits > 1) {
-      kbeg = split * p.kper;
-      kend = kbeg + p.kper < kend ? kbeg + p.kper : kend;
+      kbeg = split * kper;
+      kend = kbeg + kper < kend ? kbeg + kper : kend;
     }
     const float* A = p.A[seg] + (int64_t)batch * p.sA[seg];
     const float* B = p.B[seg] + (int64_t)batch * p.sB[seg];
@@ -64,7 +76,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
         int m, k;
         if (p.a_kc) { k = idx & 15; m = idx >> 4; } else { m = idx & 63; k = idx >> 6; }
         const int gm = m0 + m, gk = k0 + k;
-        As[k][m] = (gm < p.M && gk < kend) ? A[(int64_t)gm * p.sam[seg] + (int64_t)gk * p.sak[seg]] : 0.f;
+        As[k][m] = (gm < Mv && gk < kend) ? A[(int64_t)gm * p.sam[seg] + (int64_t)gk * p.sak[seg]] : 0.f;
         int n;
         if (p.b_kc) { k = idx & 15; n = idx >> 4; } else { n = idx & 63; k = idx >> 6; }
         const int gn = n0 + n;
@@ -91,7 +103,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDevF p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int row = m0 + ty * 4 + i;
-    if (row >= p.M) continue;
+    if (row >= Mv) continue;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int col = n0 + tx * 4 + j;
@@ -156,6 +168,10 @@ hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st) {
   d.partial = g.partial;
   d.a_kc = g.a_kc;
   d.b_kc = g.b_kc;
+  if (g.M_dev && g.batch != 1) return hipErrorInvalidValue;
+  if (g.K_dev && g.K[1] != 0) return hipErrorInvalidValue;
+  d.M_dev = g.M_dev;
+  d.K_dev = g.K_dev;
   const int ktiles = (g.K[0] + FK - 1) / FK;
   d.kper = ((ktiles + g.splits - 1) / g.splits) * FK;
   if (g.splits > 1 && (int64_t)d.kper * (g.splits - 1) >= g.K[0]) return hipErrorInvalidValue;
@@ -171,10 +187,15 @@ __global__ __launch_bounds__(256) void splitk_combine_kernel(const float* __rest
                                                             int64_t sC, const TIn* bias, const float* gate,
                                                             int64_t ldg, int act_tanh, int accumulate,
                                                             float* C_dact, uint32_t drop_thr, float drop_scale,
-                                                            uint64_t drop_seed) {
-  const int64_t mn = (int64_t)M * N;
+                                                            uint64_t drop_seed, const int32_t* M_dev,
+                                                            int dyn_ktiles, int dyn_blocks) {
+  const int64_t mn = (int64_t)M * N;      // extent of one partial
+  const int Mv = dev_bound_f(M_dev, M);
+  const int64_t mn_valid = (int64_t)Mv * N;   // rows the product wrote
+  if (dyn_ktiles > 0)   // the product chose its split from the row count: the same choice here
+    splits = pp_dyn_splits(((Mv + 255) / 256) * ((N + 255) / 256), dyn_ktiles, splits, dyn_blocks);
   const int batch = blockIdx.y;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn; i += (int64_t)gridDim.x * 256) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < mn_valid; i += (int64_t)gridDim.x * 256) {
     const int row = (int)(i / N), col = (int)(i - (int64_t)row * N);
     const float* P = partial + (int64_t)batch * splits * mn + i;
     float v = 0.f;
@@ -205,6 +226,9 @@ __global__ __launch_bounds__(256) void splitk_combine_kernel(const float* __rest
 
 hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st) {
   const int64_t mn = (int64_t)g.M * g.N;
+  // a split chosen by the persistent kernel (dyn_split): its reduction tiles and its grid, as that launch had them
+  const int dyn_ktiles = g.dyn_split ? (g.K[0] + 63) / 64 : 0;
+  const int dyn_blocks = g.dyn_split ? pp_grid_blocks(((g.M + 255) / 256) * ((g.N + 255) / 256) * g.splits) : 0;
   int blocks = (int)((mn + 255) / 256);
   if (blocks > 8192) blocks = 8192;
   dim3 grid(blocks, g.batch);
@@ -214,15 +238,16 @@ hipError_t launch_splitk_combine(const GemmArgs& g, bool in_bf16, hipStream_t st
     if (g.c_bf16)
       hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, true>), grid, dim3(256), 0, st, g.partial, g.splits,
                          g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact,
-                         g.drop_thr, g.drop_scale, g.drop_seed);
+                         g.drop_thr, g.drop_scale, g.drop_seed, g.M_dev, dyn_ktiles, dyn_blocks);
     else
       hipLaunchKernelGGL((splitk_combine_kernel<uint16_t, false>), grid, dim3(256), 0, st, g.partial, g.splits,
                          g.M, g.N, g.C, g.C_lo, g.ldc, g.sC, bias, gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact,
-                         g.drop_thr, g.drop_scale, g.drop_seed);
+                         g.drop_thr, g.drop_scale, g.drop_seed, g.M_dev, dyn_ktiles, dyn_blocks);
   } else {
     hipLaunchKernelGGL((splitk_combine_kernel<float, false>), grid, dim3(256), 0, st, g.partial, g.splits, g.M,
                        g.N, g.C, g.C_lo, g.ldc, g.sC, reinterpret_cast<const float*>(g.bias),
-                       g.gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact, g.drop_thr, g.drop_scale, g.drop_seed);
+                       g.gate, g.ldg, g.act_tanh, g.accumulate, g.C_dact, g.drop_thr, g.drop_scale, g.drop_seed,
+                       g.M_dev, dyn_ktiles, dyn_blocks);
   }
   return hipGetLastError();
 }

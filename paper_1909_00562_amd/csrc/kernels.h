@@ -20,20 +20,36 @@ hipError_t launch_attn_softmax_rows_bwd(const float* alpha32, const float* dalph
                                         void* dscoreE, void* dscoreE_lo, int64_t ldS, bool e_bf16,
                                         hipStream_t st);
 
+// Row compaction (rows / n_act below, both null = off): logits, lse and tok_loss_ws hold only the *n_act rows
+// whose target is not padding, row r being position rows[r]; N stays the bound the launch is sized for.
+// Position n -> row_pos[n] (its compacted row, -1 at padding), the list rows[0 .. *n_act) of positions in
+// increasing order, *n_act; optional per-position outputs: tgt_mask everywhere, tok_loss = 0 and
+// argmax = pad_id at padding (the statistics kernel fills the other positions).
+hipError_t launch_row_compact(const int32_t* targets, int N, int V, int pad_id, int32_t* row_pos, int32_t* rows,
+                              int32_t* n_act, uint8_t* tgt_mask, float* tok_loss, int32_t* argmax, hipStream_t st);
+// dst_x[r] = src_x[rows[r]], r < *n_act; rows of bytes_x bytes (multiples of 4); the second array is optional
+hipError_t launch_gather_rows(const int32_t* rows, const int32_t* n_act, int N, const void* src0, void* dst0,
+                              int64_t bytes0, const void* src1, void* dst1, int64_t bytes1, hipStream_t st);
+// dst_x[n] = src_x[row_pos[n]], zeros where row_pos[n] < 0; all N rows of dst are written; second array optional
+hipError_t launch_scatter_rows(const int32_t* row_pos, int N, const void* src0, void* dst0, const void* src1,
+                               void* dst1, int64_t bytes, hipStream_t st);
+
 // Eq. 5-6 per row n of logits [N,ldV]: lse, loss, argmax, target mask.
 hipError_t launch_xent_stats(const void* logits, int64_t ldV, bool e_bf16, int N, int V,
                              const int32_t* targets, int pad_id, float* lse, float* tok_loss_ws,
-                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, hipStream_t st);
-// loss_sum = sum(tok_loss_ws) in double, n_tok = number of non-pad targets; fixed order.
+                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, const int32_t* rows,
+                             const int32_t* n_act, hipStream_t st);
+// loss_sum = sum(tok_loss_ws) in double, n_tok = number of non-pad targets (= *n_act when given); fixed order.
 hipError_t launch_loss_reduce(const float* tok_loss_ws, const int32_t* targets, int N, int V, int pad_id,
-                              float* loss_sum, int32_t* n_tok, hipStream_t st);
+                              float* loss_sum, int32_t* n_tok, const int32_t* n_act, hipStream_t st);
 
 // rows of logits handled by one block of the dlogits kernel (also sizes db_partial)
 int xent_rows_per_block(int N, int V, bool e_bf16);
 // dlogits = g * (exp(logit - lse) - onehot) on non-pad rows, 0 on pad rows and on
 // columns V..ldV-1, in place; db_partial[rb][v] = column sums of row block rb.
 hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, int V, const int32_t* targets,
-                               int pad_id, const float* lse, float g, float* db_partial, hipStream_t st);
+                               int pad_id, const float* lse, float g, float* db_partial, const int32_t* rows,
+                               const int32_t* n_act, hipStream_t st);
 // db_out[v] = sum_rb db_partial[rb][v]
 hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st);
 

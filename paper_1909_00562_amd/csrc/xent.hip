@@ -55,9 +55,15 @@ __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ 
                                                         const int32_t* __restrict__ targets, int pad_id,
                                                         float* __restrict__ lse, float* __restrict__ tok_loss_ws,
                                                         float* __restrict__ tok_loss, int32_t* __restrict__ argmax,
-                                                        uint8_t* __restrict__ tgt_mask) {
+                                                        uint8_t* __restrict__ tgt_mask,
+                                                        const int32_t* __restrict__ rows,
+                                                        const int32_t* __restrict__ n_act) {
   constexpr int VEC = Vec<TE>::N;
+  // compacted rows (rows != null): logits row r belongs to position rows[r]; lse and the workspace loss are
+  // indexed by r, the caller's per-position outputs by the position
   const int n = blockIdx.x, tid = threadIdx.x;
+  if (rows && n >= *n_act) return;
+  const int pos = rows ? rows[n] : n;
   const TE* x = logits + (int64_t)n * ldV;
   RowStat st{-INFINITY, 0.f, 0x7fffffff};
   for (int v0 = tid * VEC; v0 < V; v0 += 256 * VEC) {
@@ -95,29 +101,36 @@ __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ 
   if (tid == 0) {
     RowStat r = combine(combine(ws[0], ws[1]), combine(ws[2], ws[3]));
     const float l = r.m + logf(r.s);
-    const int y = targets[n];
+    const int y = targets[pos];
     const bool nonpad = (y != pad_id) && (y >= 0) && (y < V);
     const float loss = nonpad ? l - ld_elem<TE>(x, y) : 0.f;
     lse[n] = l;
     tok_loss_ws[n] = loss;
-    if (tok_loss) tok_loss[n] = loss;
-    if (argmax) argmax[n] = r.idx;
-    if (tgt_mask) tgt_mask[n] = nonpad ? 1 : 0;
+    if (tok_loss) tok_loss[pos] = loss;
+    if (argmax) argmax[pos] = r.idx;
+    if (tgt_mask) tgt_mask[pos] = nonpad ? 1 : 0;
   }
 }
 
 __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ tok_loss_ws,
                                                           const int32_t* __restrict__ targets, int N, int V,
-                                                          int pad_id, float* loss_sum, int32_t* n_tok) {
+                                                          int pad_id, float* loss_sum, int32_t* n_tok,
+                                                          const int32_t* __restrict__ n_act) {
   __shared__ double sd[1024];
   __shared__ int sc[1024];
   const int tid = threadIdx.x;
   double acc = 0.0;
   int cnt = 0;
-  for (int i = tid; i < N; i += 1024) {
-    acc += (double)tok_loss_ws[i];
-    const int y = targets[i];
-    cnt += ((y != pad_id) && (y >= 0) && (y < V)) ? 1 : 0;
+  if (n_act) {   // compacted rows: the first *n_act entries are the non-pad positions
+    const int na = *n_act;
+    for (int i = tid; i < na; i += 1024) acc += (double)tok_loss_ws[i];
+    cnt = tid == 0 ? na : 0;
+  } else {
+    for (int i = tid; i < N; i += 1024) {
+      acc += (double)tok_loss_ws[i];
+      const int y = targets[i];
+      cnt += ((y != pad_id) && (y >= 0) && (y < V)) ? 1 : 0;
+    }
   }
   sd[tid] = acc;
   sc[tid] = cnt;
@@ -133,11 +146,14 @@ template <typename TE>
 __global__ __launch_bounds__(256) void xent_dlogits_kernel(TE* __restrict__ logits, int64_t ldV, int N, int V,
                                                           const int32_t* __restrict__ targets, int pad_id,
                                                           const float* __restrict__ lse, float g, int RB,
-                                                          float* __restrict__ db_partial) {
+                                                          float* __restrict__ db_partial,
+                                                          const int32_t* __restrict__ rows,
+                                                          const int32_t* __restrict__ n_act) {
   constexpr int VEC = Vec<TE>::N;
   const int c0 = (blockIdx.x * 256 + threadIdx.x) * VEC;
   if (c0 >= ldV) return;
-  const int r0 = blockIdx.y * RB;
+  if (rows) N = *n_act;                 // compacted rows: row r belongs to position rows[r]; blocks past the
+  const int r0 = blockIdx.y * RB;       // last row still store their (zero) column sums
   const int r1 = r0 + RB < N ? r0 + RB : N;
   float cs[VEC];
 #pragma unroll
@@ -155,7 +171,7 @@ __global__ __launch_bounds__(256) void xent_dlogits_kernel(TE* __restrict__ logi
       l[u] = 0.f;
       q[u] = make_uint4(0, 0, 0, 0);
       if (rr < r1) {
-        y[u] = targets[rr];
+        y[u] = targets[rows ? rows[rr] : rr];
         live[u] = (y[u] != pad_id) && (y[u] >= 0) && (y[u] < V);
         if (live[u]) {                      // pad rows are not read, only zeroed
           l[u] = lse[rr];
@@ -196,22 +212,23 @@ __global__ __launch_bounds__(256) void db_reduce_kernel(const float* __restrict_
 // ---- launchers ----------------------------------------------------------------
 hipError_t launch_xent_stats(const void* logits, int64_t ldV, bool e_bf16, int N, int V,
                              const int32_t* targets, int pad_id, float* lse, float* tok_loss_ws,
-                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, hipStream_t st) {
+                             float* tok_loss, int32_t* argmax, uint8_t* tgt_mask, const int32_t* rows,
+                             const int32_t* n_act, hipStream_t st) {
   if (e_bf16)
     hipLaunchKernelGGL(xent_stats_kernel<uint16_t>, dim3(N), dim3(256), 0, st,
                        reinterpret_cast<const uint16_t*>(logits), ldV, V, targets, pad_id, lse, tok_loss_ws,
-                       tok_loss, argmax, tgt_mask);
+                       tok_loss, argmax, tgt_mask, rows, n_act);
   else
     hipLaunchKernelGGL(xent_stats_kernel<float>, dim3(N), dim3(256), 0, st,
                        reinterpret_cast<const float*>(logits), ldV, V, targets, pad_id, lse, tok_loss_ws, tok_loss,
-                       argmax, tgt_mask);
+                       argmax, tgt_mask, rows, n_act);
   return hipGetLastError();
 }
 
 hipError_t launch_loss_reduce(const float* tok_loss_ws, const int32_t* targets, int N, int V, int pad_id,
-                              float* loss_sum, int32_t* n_tok, hipStream_t st) {
+                              float* loss_sum, int32_t* n_tok, const int32_t* n_act, hipStream_t st) {
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, st, tok_loss_ws, targets, N, V, pad_id, loss_sum,
-                     n_tok);
+                     n_tok, n_act);
   return hipGetLastError();
 }
 
@@ -226,16 +243,17 @@ int xent_rows_per_block(int N, int V, bool e_bf16) {
 }
 
 hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, int V, const int32_t* targets,
-                               int pad_id, const float* lse, float g, float* db_partial, hipStream_t st) {
+                               int pad_id, const float* lse, float g, float* db_partial, const int32_t* rows,
+                               const int32_t* n_act, hipStream_t st) {
   const int vec = e_bf16 ? 8 : 4;
   const int RB = xent_rows_per_block(N, V, e_bf16);
   dim3 grid((unsigned)((ldV + 256 * vec - 1) / (256 * vec)), (N + RB - 1) / RB);
   if (e_bf16)
     hipLaunchKernelGGL(xent_dlogits_kernel<uint16_t>, grid, dim3(256), 0, st, reinterpret_cast<uint16_t*>(logits),
-                       ldV, N, V, targets, pad_id, lse, g, RB, db_partial);
+                       ldV, N, V, targets, pad_id, lse, g, RB, db_partial, rows, n_act);
   else
     hipLaunchKernelGGL(xent_dlogits_kernel<float>, grid, dim3(256), 0, st, reinterpret_cast<float*>(logits), ldV, N,
-                       V, targets, pad_id, lse, g, RB, db_partial);
+                       V, targets, pad_id, lse, g, RB, db_partial, rows, n_act);
   return hipGetLastError();
 }
 

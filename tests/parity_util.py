@@ -50,12 +50,29 @@ def _host(t):
 class GpuRun:
     """fwd (+ bwd) of the HIP library on `inp`, outputs fetched on demand."""
 
-    def __init__(self, inp, batch=None):
+    def __init__(self, inp, batch=None, skip_pad_rows=False):
         import paper_1909_00562_amd as lib
         from paper_1909_00562_amd import binding as bd
         self.bd = bd
         self.inp = inp
-        self.db = batch if batch is not None else lib.DeviceBatch(inp)
+        self.db = batch if batch is not None else lib.DeviceBatch(inp, skip_pad_rows=skip_pad_rows)
+        self.compact = self.db.shape.skip_pad_rows != 0
+
+    def _by_position(self, which, sel, fill):
+        """A per-row saved activation as [T, len(sel), ...].  With row compaction the library holds one row per
+        non-pad position: those rows are put at their positions and the padding positions get `fill`."""
+        bd, db = self.bd, self.db
+        v = db.view(which)
+        if not self.compact:
+            return _host(v[:, sel])
+        pos = db.view(bd.AS_VIEW_ROW_POS)[:, sel]                  # [T, nsel] int32, -1 at padding
+        n_act = int(db.n_tok.item())
+        live = pos >= 0
+        assert int(pos.max().item()) < n_act if bool(live.any()) else True
+        rows = v[pos.clamp(min=0).long().reshape(-1)]              # gather on the device
+        out = _host(rows).reshape(tuple(pos.shape) + tuple(v.shape[1:]))
+        out[~_host(live).astype(bool)] = fill
+        return out
 
     def fwd(self, sentences=None, logits=True):
         bd, db = self.bd, self.db
@@ -63,12 +80,17 @@ class GpuRun:
         db.sync()
         sel = slice(None) if sentences is None else list(sentences)
         f = dict(alpha=_host(db.view(bd.AS_VIEW_ALPHA)[sel]), ctx=_host(db.view(bd.AS_VIEW_CTX)[:, sel]),
-                 h_c=_host(db.view(bd.AS_VIEW_HC)[:, sel]), lse=_host(db.view(bd.AS_VIEW_LSE)[:, sel]),
+                 h_c=_host(db.view(bd.AS_VIEW_HC)[:, sel]), lse=self._by_position(bd.AS_VIEW_LSE, sel, np.nan),
                  tok_loss=_host(db.tok_loss[:, sel]), argmax=_host(db.argmax[:, sel]),
                  attn_mask=_host(db.attn_mask[sel]), tgt_mask=_host(db.tgt_mask[:, sel]),
                  loss_sum=float(db.loss_sum.item()), n_tok=int(db.n_tok.item()))
+        if self.compact:   # the row map itself: non-pad positions numbered in increasing n, -1 elsewhere
+            pos = _host(db.view(bd.AS_VIEW_ROW_POS)).reshape(-1)
+            tm = _host(db.tgt_mask).reshape(-1).astype(bool)
+            assert np.array_equal(pos[tm], np.arange(int(tm.sum()))) and np.all(pos[~tm] == -1), "row map"
+            assert f["n_tok"] == int(tm.sum())
         if logits:
-            f["logits"] = _host(db.view(bd.AS_VIEW_LOGITS)[:, sel])
+            f["logits"] = self._by_position(bd.AS_VIEW_LOGITS, sel, np.nan)
         return f
 
     def bwd(self, sentences=None, dlogits=False):
@@ -79,7 +101,7 @@ class GpuRun:
         g = dict(d_h_dec=_host(db.d_h_dec[:, sel]), d_h_enc=_host(db.d_h_enc[:, sel]), dW_a=_host(db.dW_a),
                  dW_c=_host(db.dW_c), dW_out=_host(db.dW_out), db_out=_host(db.db_out))
         if dlogits:
-            g["dlogits"] = _host(db.view(bd.AS_VIEW_LOGITS)[:, sel])
+            g["dlogits"] = self._by_position(bd.AS_VIEW_LOGITS, sel, 0.0)   # no row = the zero row of a pad position
         return g
 
 
@@ -125,18 +147,28 @@ def assert_close(x, o, dtype, name, log=None):
     return s
 
 
-def check_argmax(gpu_argmax, gpu_logits, oracle_logits, tgt_mask, dtype):
+def check_argmax(gpu_argmax, gpu_logits, oracle_logits, tgt_mask, dtype, pad_rows_hold=None):
     """Argmax rule: (1) bit exact against "lowest id attaining the maximum"
     applied to the logits the GPU stored (both sides take the decision in the
     kernel's precision); (2) at non-pad rows whose oracle top-1/top-2 gap
     exceeds twice the logits tolerance, equal to the oracle's argmax; (3) at the
     remaining rows the chosen id's oracle logit lies within that band of the
-    maximum.  Returns (#rows with a clear maximum, #rows inside the band)."""
+    maximum.  With row compaction no logits exist at padding positions and the
+    library reports `pad_rows_hold` (the pad id) there.
+    Returns (#rows with a clear maximum, #rows inside the band)."""
     V = oracle_logits.shape[-1]
     ol = oracle_logits.reshape(-1, V)
-    own = gpu_logits.reshape(-1, V).argmax(axis=1)          # numpy: first maximiser
-    assert np.array_equal(own, gpu_argmax.reshape(-1)), "argmax differs from first maximiser of stored logits"
     rows = np.nonzero(tgt_mask.reshape(-1))[0]
+    gl = gpu_logits.reshape(-1, V)
+    ga = gpu_argmax.reshape(-1)
+    if pad_rows_hold is None:
+        own = gl.argmax(axis=1)                             # numpy: first maximiser
+        assert np.array_equal(own, ga), "argmax differs from first maximiser of stored logits"
+    else:
+        assert np.array_equal(gl[rows].argmax(axis=1), ga[rows]), "argmax differs from first maximiser of stored logits"
+        pad = np.ones(len(ga), dtype=bool)
+        pad[rows] = False
+        assert np.all(ga[pad] == pad_rows_hold), "argmax at padding positions"
     if len(rows) == 0 or V < 2:
         return 0, 0
     sub = ol[rows]
@@ -154,7 +186,7 @@ def check_argmax(gpu_argmax, gpu_logits, oracle_logits, tgt_mask, dtype):
     return int(clear.sum()), int(len(rows) - clear.sum())
 
 
-def compare_all(f, g, fo, go, dtype, log=None, check_logits=True):
+def compare_all(f, g, fo, go, dtype, log=None, check_logits=True, pad_rows_hold=None):
     """Full comparison of one GPU run against the oracle on the same batch."""
     assert np.array_equal(f["attn_mask"], fo["attn_mask"]), "attn_mask"
     assert np.array_equal(f["tgt_mask"], fo["tgt_mask"]), "tgt_mask"
@@ -175,7 +207,7 @@ def compare_all(f, g, fo, go, dtype, log=None, check_logits=True):
     assert np.all(f["tok_loss"][~m] == 0.0), "tok_loss at pad rows"
     if check_logits and "logits" in f:
         assert_close(f["logits"][m], fo["logits"][m], dtype, "logits", log)
-        check_argmax(f["argmax"], f["logits"], fo["logits"], fo["tgt_mask"], dtype)
+        check_argmax(f["argmax"], f["logits"], fo["logits"], fo["tgt_mask"], dtype, pad_rows_hold)
     if g is not None:
         for k in ("d_h_dec", "d_h_enc", "dW_a", "dW_c", "dW_out", "db_out"):
             assert_close(g[k], go[k], dtype, k, log)
