@@ -26,7 +26,7 @@ STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "g
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
            "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
-           "attn_softmax_step_fwd"]
+           "attn_softmax_step_fwd", "lstm_stack_workspace_bytes", "lstm_stack_fwd", "lstm_stack_bwd"]
 
 
 class AttnSoftmaxError(RuntimeError):
@@ -41,6 +41,11 @@ class AsShape(ctypes.Structure):
                 ("dtype", ctypes.c_int32), ("grad_scale", ctypes.c_float),
                 ("dropout_p", ctypes.c_float), ("dropout_seed", ctypes.c_uint64),
                 ("skip_pad_rows", ctypes.c_int32)]
+
+
+class LsShape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("B", ctypes.c_int32), ("I", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("L", ctypes.c_int32), ("dtype", ctypes.c_int32)]
 
 
 class AsAdam(ctypes.Structure):
@@ -85,6 +90,12 @@ def load_library():
     lib.attn_softmax_step_fwd.argtypes = [ctypes.POINTER(AsShape)] + [vp] * 11 + [vp, sz, vp]
     lib.attn_softmax_adam_step.restype = ctypes.c_int
     lib.attn_softmax_adam_step.argtypes = [ctypes.POINTER(AsAdam), sz, vp, vp, vp, vp, vp, ctypes.c_int32, vp]
+    lib.lstm_stack_workspace_bytes.restype = sz
+    lib.lstm_stack_workspace_bytes.argtypes = [ctypes.POINTER(LsShape)]
+    lib.lstm_stack_fwd.restype = ctypes.c_int
+    lib.lstm_stack_fwd.argtypes = [ctypes.POINTER(LsShape)] + [vp] * 10 + [vp, sz, vp]
+    lib.lstm_stack_bwd.restype = ctypes.c_int
+    lib.lstm_stack_bwd.argtypes = [ctypes.POINTER(LsShape)] + [vp] * 7 + [vp, sz] + [vp] * 6 + [vp]
     _lib = lib
     return lib
 
@@ -170,6 +181,43 @@ def attn_softmax_adam_step(hyper: AsAdam, n: int, grad, master, m, v, weights_ou
                            check=True) -> int:
     rc = load_library().attn_softmax_adam_step(ctypes.byref(hyper) if hyper is not None else None, n, _ptr(grad),
                                                _ptr(master), _ptr(m), _ptr(v), _ptr(weights_out), dtype, stream)
+    if check:
+        _check(rc)
+    return rc
+
+
+def _ptr_array(tensors):
+    """Host array of device addresses (one per layer); None stays NULL."""
+    if tensors is None:
+        return None
+    arr = (ctypes.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+    return ctypes.cast(arr, ctypes.c_void_p), arr      # the second element keeps the array alive
+
+
+def lstm_stack_workspace_bytes(shape: LsShape) -> int:
+    return int(load_library().lstm_stack_workspace_bytes(ctypes.byref(shape)))
+
+
+def lstm_stack_fwd(shape, x, lengths, W_ih, W_hh, b, h0, c0, y, hT, cT, workspace, workspace_bytes, stream=0,
+                   check=True) -> int:
+    """W_ih, W_hh, b: sequences of L device tensors (or addresses)."""
+    arrs = [_ptr_array(a) for a in (W_ih, W_hh, b)]
+    rc = load_library().lstm_stack_fwd(ctypes.byref(shape) if shape is not None else None, _ptr(x), _ptr(lengths),
+                                       *[a[0] if a else None for a in arrs], _ptr(h0), _ptr(c0), _ptr(y), _ptr(hT),
+                                       _ptr(cT), _ptr(workspace), int(workspace_bytes), stream or None)
+    if check:
+        _check(rc)
+    return rc
+
+
+def lstm_stack_bwd(shape, x, lengths, W_ih, W_hh, dy, dhT, dcT, workspace, workspace_bytes, dx, dW_ih, dW_hh, db,
+                   dh0, dc0, stream=0, check=True) -> int:
+    ins = [_ptr_array(a) for a in (W_ih, W_hh)]
+    outs = [_ptr_array(a) for a in (dW_ih, dW_hh, db)]
+    rc = load_library().lstm_stack_bwd(ctypes.byref(shape) if shape is not None else None, _ptr(x), _ptr(lengths),
+                                       *[a[0] if a else None for a in ins], _ptr(dy), _ptr(dhT), _ptr(dcT),
+                                       _ptr(workspace), int(workspace_bytes), _ptr(dx),
+                                       *[a[0] if a else None for a in outs], _ptr(dh0), _ptr(dc0), stream or None)
     if check:
         _check(rc)
     return rc
@@ -264,6 +312,65 @@ class DeviceBatch:
                 return raw.view(self.tdt).view(T * B, ld)[:, :V]
             return raw.view(self.tdt).view(T, B, ld)[:, :, :V]
         raise ValueError(which)
+
+    def sync(self):
+        self.torch.cuda.synchronize(self.dev)
+
+
+class DeviceLstm:
+    """Device buffers for one side (encoder or decoder) of the stacked LSTM: uploads the inputs, owns the
+    outputs and the workspace, and forwards to the C ABI.  No arithmetic happens here.
+    x [T,B,I], lengths [B], W_ih / W_hh / b: lists of L arrays, h0 / c0 [L,B,H] or None (numpy, values already
+    representable in the storage type)."""
+
+    def __init__(self, x, lengths, W_ih, W_hh, b, h0=None, c0=None, dtype="f32", device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.dev = torch.device(device)
+        bf = dtype == "bf16"
+        tdt = torch.bfloat16 if bf else torch.float32
+        self.tdt = tdt
+        T, B, I = x.shape
+        L, H = len(W_ih), W_hh[0].shape[1]
+        self.T, self.B, self.I, self.H, self.L = T, B, I, H, L
+        self.shape = LsShape(T, B, I, H, L, AS_BF16 if bf else AS_F32)
+        f32 = torch.float32
+
+        def up(a, dt=tdt):
+            return torch.from_numpy(np.ascontiguousarray(a)).to(dt).to(self.dev)
+
+        self.x = up(x)
+        self.lengths = torch.from_numpy(np.asarray(lengths, dtype=np.int32)).to(self.dev)
+        self.W_ih = [up(w) for w in W_ih]
+        self.W_hh = [up(w) for w in W_hh]
+        self.b = [up(v) for v in b]
+        self.h0 = up(h0, f32) if h0 is not None else None
+        self.c0 = up(c0, f32) if c0 is not None else None
+        self.y = torch.empty(T, B, H, dtype=tdt, device=self.dev)
+        self.hT = torch.empty(L, B, H, dtype=f32, device=self.dev)
+        self.cT = torch.empty(L, B, H, dtype=f32, device=self.dev)
+        self.ws_bytes = lstm_stack_workspace_bytes(self.shape)
+        if self.ws_bytes == 0:
+            raise AttnSoftmaxError(2, "invalid shape for the LSTM workspace")
+        self.workspace = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        self.dx = torch.empty(T, B, I, dtype=f32, device=self.dev)
+        self.dW_ih = [torch.empty(w.shape, dtype=f32, device=self.dev) for w in self.W_ih]
+        self.dW_hh = [torch.empty(w.shape, dtype=f32, device=self.dev) for w in self.W_hh]
+        self.db = [torch.empty(v.shape, dtype=f32, device=self.dev) for v in self.b]
+        self.dh0 = torch.empty(L, B, H, dtype=f32, device=self.dev)
+        self.dc0 = torch.empty(L, B, H, dtype=f32, device=self.dev)
+
+    def _stream(self) -> int:
+        return int(self.torch.cuda.current_stream(self.dev).cuda_stream)
+
+    def fwd(self):
+        lstm_stack_fwd(self.shape, self.x, self.lengths, self.W_ih, self.W_hh, self.b, self.h0, self.c0, self.y,
+                       self.hT, self.cT, self.workspace, self.ws_bytes, self._stream())
+
+    def bwd(self, dy, dhT=None, dcT=None):
+        """dy [T,B,H], dhT / dcT [L,B,H]: float32 device tensors (or None)."""
+        lstm_stack_bwd(self.shape, self.x, self.lengths, self.W_ih, self.W_hh, dy, dhT, dcT, self.workspace,
+                       self.ws_bytes, self.dx, self.dW_ih, self.dW_hh, self.db, self.dh0, self.dc0, self._stream())
 
     def sync(self):
         self.torch.cuda.synchronize(self.dev)

@@ -13,6 +13,7 @@
 
 #include "gemm.h"
 #include "kernels.h"
+#include "status.h"
 
 namespace {
 
@@ -27,6 +28,20 @@ as_status fail(as_status code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+}  // namespace
+
+namespace asx {
+as_status set_error(as_status code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+}  // namespace asx
+
+namespace {
+using namespace asx;
 
 // ---- profiling: HIP events around every launch ---------------------------------
 struct Prof {

@@ -1,0 +1,458 @@
+// Stacked LSTM without input feeding (section 3.2, Fig. 3; cell as stated in
+// include/lstm_stack.h): forward and backward over all steps of one side.
+//
+// Per layer, forward: the input half of the gate pre-activations of ALL steps is
+// one large product (X W_ih^T + b, [T*B, 4H]); then one step after the other adds
+// the recurrent half (h_{t-1} W_hh^T) and applies the cell.  Backward walks the
+// steps in reverse (cell derivative, then dh_{t-1} = da_t W_hh), after which the
+// weight gradients and the gradient of the layer's input are again large
+// products over all steps at once.  Right-padded sentences keep their state at
+// steps t >= lengths[b]; their gate gradients are zero rows, so the large
+// products need no masking.
+#include "../../include/lstm_stack.h"
+
+#include <vector>
+
+#include "common.h"
+#include "gemm.h"
+#include "kernels.h"
+#include "status.h"
+
+namespace asx {
+
+__device__ __forceinline__ float sigmoid_f(float a) { return 1.f / (1.f + expf(-a)); }
+
+// state before the first step: h (float, and rounded to the storage type as the operand of step 0), c
+template <typename TE>
+__global__ __launch_bounds__(256) void lstm_init_kernel(const float* __restrict__ h0, const float* __restrict__ c0,
+                                                       int n, float* __restrict__ hf, float* __restrict__ cs0,
+                                                       TE* __restrict__ hE0, TE* __restrict__ hL0) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float h = h0 ? h0[i] : 0.f;
+  hf[i] = h;
+  st_elem<TE>(hE0, i, h);
+  if (hL0) st_elem<TE>(hL0, i, h - round_elem<TE>(h));
+  cs0[i] = c0 ? c0[i] : 0.f;
+}
+
+// G [B,4H]: in = gate pre-activations of step t, out = i, f, g, o (kept for the backward pass).
+// hf: running float h; hE_prev / hE_new: h before / after the step in the storage type (operand of the
+// next step's product and of dW_hh); out: the layer's output of step t (0 at padded steps).
+// hL_* / out_lo (bf16 storage only, else null): what the rounding of hE_* / out lost, carried as a second
+// operand so that neither the recurrence over the steps nor the stack of layers compounds bf16 rounding.
+template <typename TE>
+__global__ __launch_bounds__(256) void lstm_cell_fwd_kernel(float* __restrict__ G, const float* __restrict__ c_prev,
+                                                           float* __restrict__ c_new, float* __restrict__ hf,
+                                                           const TE* __restrict__ hE_prev, TE* __restrict__ hE_new,
+                                                           const TE* __restrict__ hL_prev, TE* __restrict__ hL_new,
+                                                           TE* __restrict__ out, TE* __restrict__ out_lo,
+                                                           const int32_t* __restrict__ lengths, int t, int T, int B,
+                                                           int H) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * H) return;
+  const int b = idx / H, j = idx - b * H;
+  int len = lengths[b];
+  len = len < 0 ? 0 : (len > T ? T : len);
+  float* g4 = G + (int64_t)b * 4 * H + j;
+  const float i = sigmoid_f(g4[0]), f = sigmoid_f(g4[H]), g = tanhf(g4[2 * H]), o = sigmoid_f(g4[3 * H]);
+  g4[0] = i; g4[H] = f; g4[2 * H] = g; g4[3 * H] = o;
+  const float cp = c_prev[idx];
+  if (t < len) {
+    const float cn = f * cp + i * g;
+    const float hn = o * tanhf(cn);
+    c_new[idx] = cn;
+    hf[idx] = hn;
+    st_elem<TE>(hE_new, idx, hn);
+    st_elem<TE>(out, idx, hn);
+    if (hL_new) {
+      const float lo = hn - round_elem<TE>(hn);
+      st_elem<TE>(hL_new, idx, lo);
+      if (out_lo) st_elem<TE>(out_lo, idx, lo);
+    }
+  } else {
+    c_new[idx] = cp;
+    hE_new[idx] = hE_prev[idx];
+    st_elem<TE>(out, idx, 0.f);
+    if (hL_new) {
+      hL_new[idx] = hL_prev[idx];
+      if (out_lo) st_elem<TE>(out_lo, idx, 0.f);
+    }
+  }
+}
+
+// dhs / dcs: gradient w.r.t. the state after step t (in) and, for dcs, after step t-1 (out).  Valid rows write
+// their gate gradients da_t (storage type: operand of the products that follow) and clear dhs, which the
+// product da_t W_hh then fills; padded rows write zero gate gradients and pass dhs, dcs through.
+template <typename TE>
+__global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const float* __restrict__ gates,
+                                                           const float* __restrict__ c_prev,
+                                                           const float* __restrict__ c_new,
+                                                           const float* __restrict__ dout_t, float* __restrict__ dhs,
+                                                           float* __restrict__ dcs, TE* __restrict__ dG_t,
+                                                           TE* __restrict__ dGlo_t,
+                                                           const int32_t* __restrict__ lengths, int t, int T, int B,
+                                                           int H) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= B * H) return;
+  const int b = idx / H, j = idx - b * H;
+  int len = lengths[b];
+  len = len < 0 ? 0 : (len > T ? T : len);
+  TE* d4 = dG_t + (int64_t)b * 4 * H + j;
+  if (t < len) {
+    const float* g4 = gates + (int64_t)b * 4 * H + j;
+    const float i = g4[0], f = g4[H], g = g4[2 * H], o = g4[3 * H];
+    const float dh = dout_t[idx] + dhs[idx];
+    const float tc = tanhf(c_new[idx]);
+    const float dc = dcs[idx] + dh * o * (1.f - tc * tc);
+    const float da[4] = {dc * g * i * (1.f - i), dc * c_prev[idx] * f * (1.f - f), dc * i * (1.f - g * g),
+                         dh * tc * o * (1.f - o)};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      st_elem<TE>(d4, (int64_t)k * H, da[k]);
+      if (dGlo_t) st_elem<TE>(dGlo_t + (int64_t)b * 4 * H + j, (int64_t)k * H, da[k] - round_elem<TE>(da[k]));
+    }
+    dcs[idx] = dc * f;
+    dhs[idx] = 0.f;
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      st_elem<TE>(d4, (int64_t)k * H, 0.f);
+      if (dGlo_t) st_elem<TE>(dGlo_t + (int64_t)b * 4 * H + j, (int64_t)k * H, 0.f);
+    }
+  }
+}
+
+// dst = src, or zeros when src is null
+__global__ __launch_bounds__(256) void lstm_copy_or_zero_kernel(const float* __restrict__ src, float* __restrict__ dst,
+                                                               int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = src ? src[i] : 0.f;
+}
+
+// column sums of da [rows, cols] over blocks of 64 rows: part[rb][col]; summed by db_reduce in a fixed order
+template <typename TE>
+__global__ __launch_bounds__(256) void lstm_bias_partial_kernel(const TE* __restrict__ dG,
+                                                               const TE* __restrict__ dGlo, int rows, int cols,
+                                                               float* __restrict__ part) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= cols) return;
+  const int r0 = blockIdx.y * 64;
+  const int r1 = r0 + 64 < rows ? r0 + 64 : rows;
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    s += ld_elem<TE>(dG, (int64_t)r * cols + col);
+    if (dGlo) s += ld_elem<TE>(dGlo, (int64_t)r * cols + col);
+  }
+  part[(int64_t)blockIdx.y * cols + col] = s;
+}
+
+namespace {
+
+constexpr size_t kAlignL = 256;
+size_t upl(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct LsLayout {
+  size_t e;
+  int64_t TB, BH;
+  std::vector<size_t> gates, cs, hE, out;   // per layer
+  std::vector<size_t> hL, out_lo;           // per layer, bf16 storage only: rounding remainders of hE, out
+  size_t hf, dGE, dGlo, dhs, dcs, dio[2], dbpart, partial, total;
+  int nrb;
+  std::vector<GemmPlan> p_gx, p_dwi, p_dx;
+  GemmPlan p_rec, p_drec, p_dwh;
+};
+
+bool ls_shape_ok(const ls_shape* s) {
+  if (!s) return false;
+  if (s->T < 1 || s->B < 1 || s->I < 1 || s->H < 1 || s->L < 1 || s->L > 16) return false;
+  if (s->dtype != AS_F32 && s->dtype != AS_BF16) return false;
+  if (s->dtype == AS_BF16 && ((s->I % 8) != 0 || (s->H % 8) != 0)) return false;
+  if ((int64_t)s->T * s->B > (1 << 24) || s->H > (1 << 16) || s->I > (1 << 16)) return false;
+  if ((int64_t)s->T * s->B * 4 * s->H > ((int64_t)1 << 34)) return false;
+  return true;
+}
+
+LsLayout make_ls_layout(const ls_shape* s) {
+  LsLayout L;
+  const bool bf = s->dtype == AS_BF16;
+  const int T = s->T, B = s->B, I = s->I, H = s->H, NL = s->L;
+  L.e = bf ? 2 : 4;
+  L.TB = (int64_t)T * B;
+  L.BH = (int64_t)B * H;
+  const int TB = (int)L.TB;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += upl(bytes, kAlignL);
+    return o;
+  };
+  size_t pb = 0;
+  auto mx = [&](size_t v) { if (v > pb) pb = v; };
+  for (int l = 0; l < NL; ++l) {
+    const int Il = l == 0 ? I : H;
+    L.gates.push_back(take((size_t)TB * 4 * H * 4));
+    L.cs.push_back(take((size_t)(T + 1) * L.BH * 4));
+    L.hE.push_back(take((size_t)(T + 1) * L.BH * L.e));
+    L.out.push_back(l + 1 < NL ? take((size_t)TB * H * L.e) : 0);
+    L.hL.push_back(bf ? take((size_t)(T + 1) * L.BH * L.e) : 0);
+    L.out_lo.push_back(bf && l + 1 < NL ? take((size_t)TB * H * L.e) : 0);
+    L.p_gx.push_back(gemm_plan(TB, 4 * H, (bf && l > 0) ? 2 * Il : Il, 1, bf, false));
+    L.p_dwi.push_back(gemm_plan(4 * H, Il, TB, 1, bf, true));
+    L.p_dx.push_back(gemm_plan(TB, Il, bf ? 8 * H : 4 * H, 1, bf, false));
+    mx(gemm_partial_bytes(4 * H, Il, 1, L.p_dwi.back().splits));
+  }
+  // bf16: the state / gate-gradient operand is a (value, remainder) pair: two segments, which only the
+  // 128x128 kernel can split
+  L.p_rec = gemm_plan(B, 4 * H, bf ? 2 * H : H, 1, bf, true, bf);
+  L.p_drec = gemm_plan(B, H, bf ? 8 * H : 4 * H, 1, bf, true, bf);
+  L.p_dwh = gemm_plan(4 * H, H, TB, 1, bf, true);
+  mx(gemm_partial_bytes(B, 4 * H, 1, L.p_rec.splits));
+  mx(gemm_partial_bytes(B, H, 1, L.p_drec.splits));
+  mx(gemm_partial_bytes(4 * H, H, 1, L.p_dwh.splits));
+  L.hf = take((size_t)L.BH * 4);
+  L.dGE = take((size_t)TB * 4 * H * L.e);
+  L.dGlo = bf ? take((size_t)TB * 4 * H * L.e) : 0;
+  L.dhs = take((size_t)L.BH * 4);
+  L.dcs = take((size_t)L.BH * 4);
+  const size_t wmax = (size_t)(I > H ? I : H);
+  L.dio[0] = take((size_t)TB * wmax * 4);
+  L.dio[1] = take((size_t)TB * wmax * 4);
+  L.nrb = (TB + 63) / 64;
+  L.dbpart = take((size_t)L.nrb * 4 * H * 4);
+  L.partial = take(pb);
+  L.total = off;
+  return L;
+}
+
+bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+as_status check_ptr_array(const void* const* arr, int n, const char* name) {
+  if (!arr) return set_error(AS_ERR_NULL, "%s is NULL", name);
+  for (int l = 0; l < n; ++l) {
+    if (!arr[l]) return set_error(AS_ERR_NULL, "%s[%d] is NULL", name, l);
+    if (!al16(arr[l])) return set_error(AS_ERR_ALIGN, "%s[%d] = %p is not 16-byte aligned", name, l, arr[l]);
+  }
+  return AS_OK;
+}
+
+as_status check_ls(const ls_shape* s, void* ws, size_t ws_bytes, LsLayout* L) {
+  if (!s) return set_error(AS_ERR_NULL, "shape is NULL");
+  if (s->dtype != AS_F32 && s->dtype != AS_BF16) return set_error(AS_ERR_DTYPE, "unknown dtype %d", s->dtype);
+  if (s->dtype == AS_BF16 && s->T >= 1 && s->B >= 1 && s->I >= 1 && s->H >= 1 && ((s->I % 8) != 0 || (s->H % 8) != 0))
+    return set_error(AS_ERR_ALIGN, "AS_BF16 needs I %% 8 == 0 and H %% 8 == 0 (I=%d H=%d)", s->I, s->H);
+  if (!ls_shape_ok(s))
+    return set_error(AS_ERR_SHAPE, "bad shape T=%d B=%d I=%d H=%d L=%d", s->T, s->B, s->I, s->H, s->L);
+  if (!ws) return set_error(AS_ERR_NULL, "workspace is NULL");
+  if (!al16(ws)) return set_error(AS_ERR_ALIGN, "workspace %p is not 16-byte aligned", ws);
+  *L = make_ls_layout(s);
+  if (ws_bytes < L->total) return set_error(AS_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, L->total);
+  return AS_OK;
+}
+
+#define LS_TRY(expr)                                                                            \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) return set_error(AS_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename TE>
+as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int32_t* lengths,
+                 const void* const* W_ih, const void* const* W_hh, const void* const* b, const float* h0,
+                 const float* c0, char* y, float* hT, float* cT, char* w, hipStream_t st) {
+  const bool bf = sizeof(TE) == 2;
+  const int T = s->T, B = s->B, I = s->I, H = s->H, NL = s->L;
+  const int TB = (int)L.TB, BH = (int)L.BH;
+  const int nb = (BH + 255) / 256;
+  float* hf = reinterpret_cast<float*>(w + L.hf);
+  float* partial = reinterpret_cast<float*>(w + L.partial);
+  const char* xin = x;
+  const char* xin_lo = nullptr;   // the caller's x is exact in the storage type
+  for (int l = 0; l < NL; ++l) {
+    const int Il = l == 0 ? I : H;
+    float* gates = reinterpret_cast<float*>(w + L.gates[l]);
+    float* cs = reinterpret_cast<float*>(w + L.cs[l]);
+    TE* hE = reinterpret_cast<TE*>(w + L.hE[l]);
+    TE* out = reinterpret_cast<TE*>(l + 1 < NL ? w + L.out[l] : y);
+    TE* hL = bf ? reinterpret_cast<TE*>(w + L.hL[l]) : nullptr;
+    TE* out_lo = (bf && l + 1 < NL) ? reinterpret_cast<TE*>(w + L.out_lo[l]) : nullptr;
+    hipLaunchKernelGGL(lstm_init_kernel<TE>, dim3(nb), dim3(256), 0, st, h0 ? h0 + (size_t)l * BH : nullptr,
+                       c0 ? c0 + (size_t)l * BH : nullptr, BH, hf, cs, hE, hL);
+    LS_TRY(hipGetLastError());
+    {  // input half of the pre-activations of all steps: X W_ih^T + b
+      GemmArgs g;
+      g.seg(xin, Il, 0, W_ih[l], Il, 0, Il);
+      if (xin_lo) g.seg(xin_lo, Il, 0, W_ih[l], Il, 0, Il);
+      g.a_kc = true; g.b_kc = true;
+      g.M = TB; g.N = 4 * H; g.bias = b[l];
+      g.C = gates; g.ldc = 4 * H; g.c_bf16 = false;
+      LS_TRY(launch_gemm(g, bf, L.p_gx[l].big_tile, st));
+    }
+    for (int t = 0; t < T; ++t) {
+      float* Gt = gates + (size_t)t * B * 4 * H;
+      {  // + h_{t-1} W_hh^T
+        GemmArgs g;
+        g.seg(hE + (size_t)t * BH, H, 0, W_hh[l], H, 0, H);
+        if (hL) g.seg(hL + (size_t)t * BH, H, 0, W_hh[l], H, 0, H);
+        g.a_kc = true; g.b_kc = true;
+        g.M = B; g.N = 4 * H;
+        g.C = Gt; g.ldc = 4 * H; g.c_bf16 = false; g.accumulate = 1;
+        g.splits = L.p_rec.splits; g.partial = partial;
+        LS_TRY(launch_gemm(g, bf, L.p_rec.big_tile, st));
+      }
+      hipLaunchKernelGGL(lstm_cell_fwd_kernel<TE>, dim3(nb), dim3(256), 0, st, Gt, cs + (size_t)t * BH,
+                         cs + (size_t)(t + 1) * BH, hf, hE + (size_t)t * BH, hE + (size_t)(t + 1) * BH,
+                         hL ? hL + (size_t)t * BH : nullptr, hL ? hL + (size_t)(t + 1) * BH : nullptr,
+                         out + (size_t)t * BH, out_lo ? out_lo + (size_t)t * BH : nullptr, lengths, t, T, B, H);
+      LS_TRY(hipGetLastError());
+    }
+    if (hT) LS_TRY(hipMemcpyAsync(hT + (size_t)l * BH, hf, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
+    if (cT) LS_TRY(hipMemcpyAsync(cT + (size_t)l * BH, cs + (size_t)T * BH, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
+    xin = reinterpret_cast<const char*>(out);
+    xin_lo = reinterpret_cast<const char*>(out_lo);
+  }
+  return AS_OK;
+}
+
+template <typename TE>
+as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int32_t* lengths,
+                 const void* const* W_ih, const void* const* W_hh, const float* dy, const float* dhT,
+                 const float* dcT, char* w, float* dx, float* const* dW_ih, float* const* dW_hh, float* const* db,
+                 float* dh0, float* dc0, hipStream_t st) {
+  const bool bf = sizeof(TE) == 2;
+  const int T = s->T, B = s->B, I = s->I, H = s->H, NL = s->L;
+  const int TB = (int)L.TB, BH = (int)L.BH;
+  const int nb = (BH + 255) / 256;
+  float* partial = reinterpret_cast<float*>(w + L.partial);
+  TE* dGE = reinterpret_cast<TE*>(w + L.dGE);
+  TE* dGlo = bf ? reinterpret_cast<TE*>(w + L.dGlo) : nullptr;
+  float* dhs = reinterpret_cast<float*>(w + L.dhs);
+  float* dcs = reinterpret_cast<float*>(w + L.dcs);
+  float* dbpart = reinterpret_cast<float*>(w + L.dbpart);
+  const float* dout = dy;
+  for (int l = NL - 1; l >= 0; --l) {
+    const int Il = l == 0 ? I : H;
+    const float* gates = reinterpret_cast<const float*>(w + L.gates[l]);
+    const float* cs = reinterpret_cast<const float*>(w + L.cs[l]);
+    const TE* hE = reinterpret_cast<const TE*>(w + L.hE[l]);
+    const char* xin = l == 0 ? x : w + L.out[l - 1];
+    hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dhT ? dhT + (size_t)l * BH : nullptr, dhs, BH);
+    hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dcT ? dcT + (size_t)l * BH : nullptr, dcs, BH);
+    LS_TRY(hipGetLastError());
+    for (int t = T - 1; t >= 0; --t) {
+      TE* dGt = dGE + (size_t)t * B * 4 * H;
+      TE* dGlt = dGlo ? dGlo + (size_t)t * B * 4 * H : nullptr;
+      hipLaunchKernelGGL(lstm_cell_bwd_kernel<TE>, dim3(nb), dim3(256), 0, st, gates + (size_t)t * B * 4 * H,
+                         cs + (size_t)t * BH, cs + (size_t)(t + 1) * BH, dout + (size_t)t * BH, dhs, dcs, dGt, dGlt,
+                         lengths, t, T, B, H);
+      LS_TRY(hipGetLastError());
+      {  // dh_{t-1} (+)= da_t W_hh: valid rows were cleared, padded rows have da_t = 0 and keep theirs
+        GemmArgs g;
+        g.seg(dGt, 4 * H, 0, W_hh[l], H, 0, 4 * H);
+        if (dGlt) g.seg(dGlt, 4 * H, 0, W_hh[l], H, 0, 4 * H);
+        g.a_kc = true; g.b_kc = false;
+        g.M = B; g.N = H;
+        g.C = dhs; g.ldc = H; g.c_bf16 = false; g.accumulate = 1;
+        g.splits = L.p_drec.splits; g.partial = partial;
+        LS_TRY(launch_gemm(g, bf, L.p_drec.big_tile, st));
+      }
+    }
+    {  // dW_hh = sum_t da_t^T h_{t-1}
+      GemmArgs g;
+      g.seg(dGE, 4 * H, 0, hE, H, 0, TB);
+      g.a_kc = false; g.b_kc = false;
+      g.M = 4 * H; g.N = H;
+      g.C = dW_hh[l]; g.ldc = H; g.c_bf16 = false;
+      g.splits = L.p_dwh.splits; g.partial = partial;
+      LS_TRY(launch_gemm(g, bf, L.p_dwh.big_tile, st));
+    }
+    {  // dW_ih = sum_t da_t^T x_t
+      GemmArgs g;
+      g.seg(dGE, 4 * H, 0, xin, Il, 0, TB);
+      g.a_kc = false; g.b_kc = false;
+      g.M = 4 * H; g.N = Il;
+      g.C = dW_ih[l]; g.ldc = Il; g.c_bf16 = false;
+      g.splits = L.p_dwi[l].splits; g.partial = partial;
+      LS_TRY(launch_gemm(g, bf, L.p_dwi[l].big_tile, st));
+    }
+    hipLaunchKernelGGL(lstm_bias_partial_kernel<TE>, dim3((4 * H + 255) / 256, L.nrb), dim3(256), 0, st, dGE, dGlo, TB,
+                       4 * H, dbpart);
+    LS_TRY(hipGetLastError());
+    LS_TRY(launch_db_reduce(dbpart, L.nrb, 4 * H, db[l], st));
+    float* dinp = l == 0 ? dx : reinterpret_cast<float*>(w + L.dio[l & 1]);
+    {  // gradient of the layer's input, all steps: da W_ih
+      GemmArgs g;
+      g.seg(dGE, 4 * H, 0, W_ih[l], Il, 0, 4 * H);
+      if (dGlo) g.seg(dGlo, 4 * H, 0, W_ih[l], Il, 0, 4 * H);
+      g.a_kc = true; g.b_kc = false;
+      g.M = TB; g.N = Il;
+      g.C = dinp; g.ldc = Il; g.c_bf16 = false;
+      LS_TRY(launch_gemm(g, bf, L.p_dx[l].big_tile, st));
+    }
+    if (dh0) LS_TRY(hipMemcpyAsync(dh0 + (size_t)l * BH, dhs, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
+    if (dc0) LS_TRY(hipMemcpyAsync(dc0 + (size_t)l * BH, dcs, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
+    dout = dinp;
+  }
+  return AS_OK;
+}
+
+}  // namespace
+}  // namespace asx
+
+using namespace asx;
+
+extern "C" {
+
+size_t lstm_stack_workspace_bytes(const ls_shape* shape) {
+  if (!ls_shape_ok(shape)) return 0;
+  return make_ls_layout(shape).total;
+}
+
+as_status lstm_stack_fwd(const ls_shape* s, const void* x, const int32_t* lengths, const void* const* W_ih,
+                         const void* const* W_hh, const void* const* b, const float* h0, const float* c0, void* y,
+                         float* hT, float* cT, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  LsLayout L;
+  as_status rc = check_ls(s, workspace, workspace_bytes, &L);
+  if (rc != AS_OK) return rc;
+  if (!x || !lengths || !y) return set_error(AS_ERR_NULL, "a required pointer is NULL");
+  const void* ptrs[] = {x, lengths, y, h0, c0, hT, cT};
+  for (const void* p : ptrs)
+    if (p && !al16(p)) return set_error(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  if ((rc = check_ptr_array(W_ih, s->L, "W_ih")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(W_hh, s->L, "W_hh")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(b, s->L, "b")) != AS_OK) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char* w = reinterpret_cast<char*>(workspace);
+  if (s->dtype == AS_BF16)
+    return ls_fwd<uint16_t>(s, L, reinterpret_cast<const char*>(x), lengths, W_ih, W_hh, b, h0, c0,
+                            reinterpret_cast<char*>(y), hT, cT, w, st);
+  return ls_fwd<float>(s, L, reinterpret_cast<const char*>(x), lengths, W_ih, W_hh, b, h0, c0,
+                       reinterpret_cast<char*>(y), hT, cT, w, st);
+}
+
+as_status lstm_stack_bwd(const ls_shape* s, const void* x, const int32_t* lengths, const void* const* W_ih,
+                         const void* const* W_hh, const float* dy, const float* dhT, const float* dcT,
+                         void* workspace, size_t workspace_bytes, float* dx, float* const* dW_ih,
+                         float* const* dW_hh, float* const* db, float* dh0, float* dc0, void* hip_stream) {
+  LsLayout L;
+  as_status rc = check_ls(s, workspace, workspace_bytes, &L);
+  if (rc != AS_OK) return rc;
+  if (!x || !lengths || !dy || !dx) return set_error(AS_ERR_NULL, "a required pointer is NULL");
+  const void* ptrs[] = {x, lengths, dy, dhT, dcT, dx, dh0, dc0};
+  for (const void* p : ptrs)
+    if (p && !al16(p)) return set_error(AS_ERR_ALIGN, "pointer %p is not 16-byte aligned", p);
+  if ((rc = check_ptr_array(W_ih, s->L, "W_ih")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(W_hh, s->L, "W_hh")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(reinterpret_cast<const void* const*>(dW_ih), s->L, "dW_ih")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(reinterpret_cast<const void* const*>(dW_hh), s->L, "dW_hh")) != AS_OK) return rc;
+  if ((rc = check_ptr_array(reinterpret_cast<const void* const*>(db), s->L, "db")) != AS_OK) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char* w = reinterpret_cast<char*>(workspace);
+  if (s->dtype == AS_BF16)
+    return ls_bwd<uint16_t>(s, L, reinterpret_cast<const char*>(x), lengths, W_ih, W_hh, dy, dhT, dcT, w, dx, dW_ih,
+                            dW_hh, db, dh0, dc0, st);
+  return ls_bwd<float>(s, L, reinterpret_cast<const char*>(x), lengths, W_ih, W_hh, dy, dhT, dcT, w, dx, dW_ih, dW_hh,
+                       db, dh0, dc0, st);
+}
+
+}  // extern "C"

@@ -190,3 +190,51 @@ def make_custom(T: int, S: int, B: int, H: int, V: int, seed: int, dtype: str = 
     return Inputs(name=f"custom{seed}", dtype=dtype, T=T, S=S, B=B, H=H, V=V, pad_id=PAD_ID,
                   h_dec=h_dec, h_enc=h_enc, src_len=src_len, W_a=W_a, W_c=W_c,
                   W_out=W_out, b_out=b_out, targets=targets, grad_scale=grad_scale)
+
+
+@dataclass
+class LstmInputs:
+    """One side (encoder or decoder) of the stacked LSTM: word embeddings of all steps, sentence lengths,
+    per-layer weights, initial states, and the incoming gradients of a backward pass."""
+    dtype: str
+    T: int
+    B: int
+    I: int
+    H: int
+    L: int
+    x: np.ndarray            # [T,B,I] embeddings
+    lengths: np.ndarray      # [B]
+    W_ih: list
+    W_hh: list
+    b: list
+    h0: np.ndarray           # [L,B,H] float32
+    c0: np.ndarray
+    dy: np.ndarray           # [T,B,H] float32: gradient w.r.t. the top layer's outputs
+    dhT: np.ndarray          # [L,B,H] float32: gradient w.r.t. the final states
+    dcT: np.ndarray
+
+
+def make_lstm_inputs(T: int, B: int, I: int, H: int, L: int, seed: int, dtype: str = "f32", w: float = 0.1,
+                     min_len: int = 1, force_max: bool = True) -> LstmInputs:
+    """Stand-in for a batch of embedded sentences (Table 2 of the paper: embedding 512, hidden 1024, depth 4):
+    embeddings tanh(N(0,1)) like the hidden states of the other configurations, weights and biases U(-w, w),
+    lengths uniform in min_len..T with sentence 0 at full length, initial states and incoming gradients
+    N(0,1) scaled to 0.5 / 0.1.  Draw order: x, lengths, per layer (W_ih, W_hh, b), h0, c0, dy, dhT, dcT."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = _round_storage(np.tanh(rng.standard_normal((T, B, I))), dtype)
+    lengths = rng.integers(min_len, T + 1, size=B).astype(np.int32)
+    if force_max:
+        lengths[0] = T
+    W_ih, W_hh, b = [], [], []
+    for l in range(L):
+        W_ih.append(_round_storage(rng.uniform(-w, w, (4 * H, I if l == 0 else H)), dtype))
+        W_hh.append(_round_storage(rng.uniform(-w, w, (4 * H, H)), dtype))
+        b.append(_round_storage(rng.uniform(-w, w, (4 * H,)), dtype))
+    f32 = lambda a: a.astype(np.float32)
+    h0 = f32(0.5 * rng.standard_normal((L, B, H)))
+    c0 = f32(0.5 * rng.standard_normal((L, B, H)))
+    dy = f32(0.1 * rng.standard_normal((T, B, H)))
+    dhT = f32(0.1 * rng.standard_normal((L, B, H)))
+    dcT = f32(0.1 * rng.standard_normal((L, B, H)))
+    return LstmInputs(dtype=dtype, T=T, B=B, I=I, H=H, L=L, x=x, lengths=lengths, W_ih=W_ih, W_hh=W_hh, b=b,
+                      h0=h0, c0=c0, dy=dy, dhT=dhT, dcT=dcT)

@@ -13,9 +13,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _header_functions():
-    text = open(os.path.join(ROOT, "include", "attn_softmax.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(attn_softmax_\w+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b((?:attn_softmax|lstm_stack)_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -151,3 +157,48 @@ def test_step_mode_rejects_bad_arguments():
     assert lib.attn_softmax_step_fwd(s, None, *args[1:], n, 0, check=False) == 1
     assert lib.attn_softmax_step_fwd(s, *args, n - 1, 0, check=False) == 4
     assert lib.attn_softmax_step_fwd(s, 0x1004, *args[1:], n, 0, check=False) == 5
+
+
+# ---------------------------------------------------------------- lstm_stack_*
+def _ls(**kw):
+    d = dict(T=5, B=3, I=16, H=8, L=2, dtype=bd.AS_F32)
+    d.update(kw)
+    return bd.LsShape(d["T"], d["B"], d["I"], d["H"], d["L"], d["dtype"])
+
+
+def test_lstm_workspace_bytes():
+    assert bd.lstm_stack_workspace_bytes(_ls()) > 0
+    for bad in (dict(T=0), dict(B=0), dict(I=0), dict(H=0), dict(L=0), dict(L=17), dict(dtype=5),
+                dict(dtype=bd.AS_BF16, H=12), dict(dtype=bd.AS_BF16, I=12)):
+        assert bd.lstm_stack_workspace_bytes(_ls(**bad)) == 0, bad
+    assert bd.lstm_stack_workspace_bytes(_ls(L=4)) > bd.lstm_stack_workspace_bytes(_ls(L=2))
+
+
+def test_lstm_rejects_bad_arguments_before_any_launch():
+    # fake, aligned, never dereferenced device addresses
+    sh = _ls()
+    W = [0x1000, 0x2000]
+    ok = dict(x=0x100, lengths=0x200, W_ih=W, W_hh=W, b=W, h0=None, c0=None, y=0x300, hT=None, cT=None,
+              workspace=0x400, workspace_bytes=1 << 40)
+
+    def fwd(shape=sh, **over):
+        a = dict(ok)
+        a.update(over)
+        return bd.lstm_stack_fwd(shape, a["x"], a["lengths"], a["W_ih"], a["W_hh"], a["b"], a["h0"], a["c0"], a["y"],
+                                 a["hT"], a["cT"], a["workspace"], a["workspace_bytes"], 0, check=False)
+
+    assert fwd(shape=_ls(T=0)) == 2 and "bad shape" in bd.attn_softmax_last_error()
+    assert fwd(shape=_ls(dtype=9)) == 3
+    assert fwd(shape=_ls(dtype=bd.AS_BF16, H=12)) == 5
+    assert fwd(x=None) == 1
+    assert fwd(W_hh=None) == 1
+    assert fwd(W_ih=[0x1000, None]) == 1
+    assert fwd(b=[0x1000, 0x2004]) == 5
+    assert fwd(y=0x301) == 5
+    assert fwd(workspace_bytes=16) == 4
+    rc = bd.lstm_stack_bwd(sh, 0x100, 0x200, W, W, None, None, None, 0x400, 1 << 40, 0x500, W, W, W, None, None, 0,
+                           check=False)
+    assert rc == 1                                       # dy is required
+    rc = bd.lstm_stack_bwd(sh, 0x100, 0x200, W, W, 0x600, None, None, 0x400, 1 << 40, 0x500, W, None, W, None, None, 0,
+                           check=False)
+    assert rc == 1                                       # dW_hh is required
