@@ -58,6 +58,47 @@ hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_o
 hipError_t launch_attn_step(const void* h_t, const float* kprime, const void* h_enc, const int32_t* src_len, int B,
                             int S, int H, float* alpha, void* ctx, void* ctx_lo, bool e_bf16, uint8_t* attn_mask,
                             hipStream_t st);
+// One LSTM time step of one layer, bf16 storage, fused (cell as in include/lstm_stack.h; H % 8 == 0).
+// "Fragment-major" below: an operand X [rows, K] stored as XF[K/8][rows][8], so that the lanes holding the
+// rows of an MFMA fragment read contiguous memory.
+// Forward: WF = W_hh fragment-major with rows ordered unit*4 + gate (launch_ls_wfrag); hF_hi / hF_lo: h_{t-1}
+// [B,H] fragment-major as bf16 value and rounding remainder; G [B,4H] holds the input half of the gate
+// pre-activations (X W_ih^T + b) on entry and the gates i, f, g, o on exit; c_prev -> c_new [B,H] float;
+// hf [B,H] running float h (written at valid rows); hFn_hi / hFn_lo: h_t fragment-major (h_{t-1} at padded
+// rows); hE_new [B,H] row-major value of the same; out / out_lo (out_lo optional) [B,H] row-major: the layer's
+// output of step t, 0 at padded rows.
+struct LstmStepFwd {
+  const uint16_t* WF;
+  const uint16_t *hF_hi, *hF_lo;
+  float* G;
+  const float* c_prev;
+  float* c_new;
+  float* hf;
+  uint16_t *hFn_hi, *hFn_lo, *hE_new, *out, *out_lo;
+  const int32_t* lengths;
+  int t, T, B, H;
+};
+hipError_t launch_lstm_step_fwd(const LstmStepFwd& p, hipStream_t st);
+// Backward of step t: WTF = W_hh^T [H,4H] fragment-major (launch_ls_wfrag, backward); dGnF_hi / dGnF_lo: gate
+// gradients of step t+1 [B,4H] fragment-major (null for t = T-1); gates [B,4H], c_prev, c_new [B,H] as saved by
+// the forward step; dout_t [B,H] gradient w.r.t. the layer's output; dhT [B,H] gradient w.r.t. the final h
+// (null = 0); dcs [B,H] running gradient w.r.t. c (in: after step t, out: after step t-1); gate gradients of
+// step t: dG_hi / dG_lo [B,4H] row-major and dGF_hi / dGF_lo fragment-major.
+// t = -1: dh0_out [B,H] = gradient w.r.t. the initial h, nothing else is touched.
+struct LstmStepBwd {
+  const uint16_t* WTF;
+  const uint16_t *dGnF_hi, *dGnF_lo;
+  const float *gates, *c_prev, *c_new, *dout_t, *dhT;
+  float* dcs;
+  uint16_t *dG_hi, *dG_lo, *dGF_hi, *dGF_lo;
+  float* dh0_out;
+  const int32_t* lengths;
+  int t, T, B, H;
+};
+hipError_t launch_lstm_step_bwd(const LstmStepBwd& p, hipStream_t st);
+// W_hh [4H,H] of one layer into the fragment-major form the forward (backward = false) or backward step reads
+hipError_t launch_ls_wfrag(const void* W_hh, void* dst, int H, bool backward, hipStream_t st);
+
 // Adam, bias corrections passed as inv_bc1 = 1 / (1 - beta1^step), inv_bc2 likewise; wout optional.
 hipError_t launch_adam_step(size_t n, const float* grad, float* master, float* m, float* v, void* wout,
                             bool out_bf16, float lr, float beta1, float beta2, float eps, float inv_bc1,

@@ -22,33 +22,37 @@ namespace asx {
 
 __device__ __forceinline__ float sigmoid_f(float a) { return 1.f / (1.f + expf(-a)); }
 
-// state before the first step: h (float, and rounded to the storage type as the operand of step 0), c
+// State before the first step: h as float, c, and h in the storage type (hE0, row-major: the operand of dW_hh).
+// bf16 storage also gets h as (value, rounding remainder) in the fragment-major form [H/8][B][8] the fused
+// step kernel reads (hF_hi / hF_lo, else null).
 template <typename TE>
 __global__ __launch_bounds__(256) void lstm_init_kernel(const float* __restrict__ h0, const float* __restrict__ c0,
-                                                       int n, float* __restrict__ hf, float* __restrict__ cs0,
-                                                       TE* __restrict__ hE0, TE* __restrict__ hL0) {
+                                                       int B, int H, float* __restrict__ hf,
+                                                       float* __restrict__ cs0, TE* __restrict__ hE0,
+                                                       TE* __restrict__ hF_hi, TE* __restrict__ hF_lo) {
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+  if (i >= B * H) return;
   const float h = h0 ? h0[i] : 0.f;
   hf[i] = h;
   st_elem<TE>(hE0, i, h);
-  if (hL0) st_elem<TE>(hL0, i, h - round_elem<TE>(h));
   cs0[i] = c0 ? c0[i] : 0.f;
+  if (hF_hi) {
+    const int b = i / H, j = i - b * H;
+    const int64_t f = ((int64_t)(j >> 3) * B + b) * 8 + (j & 7);
+    st_elem<TE>(hF_hi, f, h);
+    st_elem<TE>(hF_lo, f, h - round_elem<TE>(h));
+  }
 }
 
+// fp32 storage: the cell after the recurrent product has been added by a separate launch.
 // G [B,4H]: in = gate pre-activations of step t, out = i, f, g, o (kept for the backward pass).
-// hf: running float h; hE_prev / hE_new: h before / after the step in the storage type (operand of the
-// next step's product and of dW_hh); out: the layer's output of step t (0 at padded steps).
-// hL_* / out_lo (bf16 storage only, else null): what the rounding of hE_* / out lost, carried as a second
-// operand so that neither the recurrence over the steps nor the stack of layers compounds bf16 rounding.
-template <typename TE>
+// hf: running h; h_prev / h_new: h before / after the step (operand of the next step's product and of
+// dW_hh); out: the layer's output of step t (0 at padded steps).
 __global__ __launch_bounds__(256) void lstm_cell_fwd_kernel(float* __restrict__ G, const float* __restrict__ c_prev,
                                                            float* __restrict__ c_new, float* __restrict__ hf,
-                                                           const TE* __restrict__ hE_prev, TE* __restrict__ hE_new,
-                                                           const TE* __restrict__ hL_prev, TE* __restrict__ hL_new,
-                                                           TE* __restrict__ out, TE* __restrict__ out_lo,
-                                                           const int32_t* __restrict__ lengths, int t, int T, int B,
-                                                           int H) {
+                                                           const float* __restrict__ h_prev, float* __restrict__ h_new,
+                                                           float* __restrict__ out, const int32_t* __restrict__ lengths,
+                                                           int t, int T, int B, int H) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= B * H) return;
   const int b = idx / H, j = idx - b * H;
@@ -63,34 +67,23 @@ __global__ __launch_bounds__(256) void lstm_cell_fwd_kernel(float* __restrict__ 
     const float hn = o * tanhf(cn);
     c_new[idx] = cn;
     hf[idx] = hn;
-    st_elem<TE>(hE_new, idx, hn);
-    st_elem<TE>(out, idx, hn);
-    if (hL_new) {
-      const float lo = hn - round_elem<TE>(hn);
-      st_elem<TE>(hL_new, idx, lo);
-      if (out_lo) st_elem<TE>(out_lo, idx, lo);
-    }
+    h_new[idx] = hn;
+    out[idx] = hn;
   } else {
     c_new[idx] = cp;
-    hE_new[idx] = hE_prev[idx];
-    st_elem<TE>(out, idx, 0.f);
-    if (hL_new) {
-      hL_new[idx] = hL_prev[idx];
-      if (out_lo) st_elem<TE>(out_lo, idx, 0.f);
-    }
+    h_new[idx] = h_prev[idx];
+    out[idx] = 0.f;
   }
 }
 
-// dhs / dcs: gradient w.r.t. the state after step t (in) and, for dcs, after step t-1 (out).  Valid rows write
-// their gate gradients da_t (storage type: operand of the products that follow) and clear dhs, which the
-// product da_t W_hh then fills; padded rows write zero gate gradients and pass dhs, dcs through.
-template <typename TE>
+// fp32 storage.  dhs / dcs: gradient w.r.t. the state after step t (in) and, for dcs, after step t-1 (out).
+// Valid rows write their gate gradients da_t and clear dhs, which the product da_t W_hh then fills; padded
+// rows write zero gate gradients and pass dhs, dcs through.
 __global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const float* __restrict__ gates,
                                                            const float* __restrict__ c_prev,
                                                            const float* __restrict__ c_new,
                                                            const float* __restrict__ dout_t, float* __restrict__ dhs,
-                                                           float* __restrict__ dcs, TE* __restrict__ dG_t,
-                                                           TE* __restrict__ dGlo_t,
+                                                           float* __restrict__ dcs, float* __restrict__ dG_t,
                                                            const int32_t* __restrict__ lengths, int t, int T, int B,
                                                            int H) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
@@ -98,28 +91,21 @@ __global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const float* __restr
   const int b = idx / H, j = idx - b * H;
   int len = lengths[b];
   len = len < 0 ? 0 : (len > T ? T : len);
-  TE* d4 = dG_t + (int64_t)b * 4 * H + j;
+  float* d4 = dG_t + (int64_t)b * 4 * H + j;
   if (t < len) {
     const float* g4 = gates + (int64_t)b * 4 * H + j;
     const float i = g4[0], f = g4[H], g = g4[2 * H], o = g4[3 * H];
     const float dh = dout_t[idx] + dhs[idx];
     const float tc = tanhf(c_new[idx]);
     const float dc = dcs[idx] + dh * o * (1.f - tc * tc);
-    const float da[4] = {dc * g * i * (1.f - i), dc * c_prev[idx] * f * (1.f - f), dc * i * (1.f - g * g),
-                         dh * tc * o * (1.f - o)};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      st_elem<TE>(d4, (int64_t)k * H, da[k]);
-      if (dGlo_t) st_elem<TE>(dGlo_t + (int64_t)b * 4 * H + j, (int64_t)k * H, da[k] - round_elem<TE>(da[k]));
-    }
+    d4[0] = dc * g * i * (1.f - i);
+    d4[H] = dc * c_prev[idx] * f * (1.f - f);
+    d4[2 * (int64_t)H] = dc * i * (1.f - g * g);
+    d4[3 * (int64_t)H] = dh * tc * o * (1.f - o);
     dcs[idx] = dc * f;
     dhs[idx] = 0.f;
   } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      st_elem<TE>(d4, (int64_t)k * H, 0.f);
-      if (dGlo_t) st_elem<TE>(dGlo_t + (int64_t)b * 4 * H + j, (int64_t)k * H, 0.f);
-    }
+    d4[0] = 0.f; d4[H] = 0.f; d4[2 * (int64_t)H] = 0.f; d4[3 * (int64_t)H] = 0.f;
   }
 }
 
@@ -130,7 +116,8 @@ __global__ __launch_bounds__(256) void lstm_copy_or_zero_kernel(const float* __r
   if (i < n) dst[i] = src ? src[i] : 0.f;
 }
 
-// column sums of da [rows, cols] over blocks of 64 rows: part[rb][col]; summed by db_reduce in a fixed order
+// column sums of da [rows, cols] (+ its rounding remainders, bf16 storage) over blocks of 64 rows:
+// part[rb][col]; summed by db_reduce in a fixed order
 template <typename TE>
 __global__ __launch_bounds__(256) void lstm_bias_partial_kernel(const TE* __restrict__ dG,
                                                                const TE* __restrict__ dGlo, int rows, int cols,
@@ -155,9 +142,12 @@ size_t upl(size_t x, size_t a) { return (x + a - 1) / a * a; }
 struct LsLayout {
   size_t e;
   int64_t TB, BH;
-  std::vector<size_t> gates, cs, hE, out;   // per layer
-  std::vector<size_t> hL, out_lo;           // per layer, bf16 storage only: rounding remainders of hE, out
+  std::vector<size_t> gates, cs, hE, out, out_lo;   // per layer; out_lo: bf16 storage only
   size_t hf, dGE, dGlo, dhs, dcs, dio[2], dbpart, partial, total;
+  // bf16 storage: fragment-major operands of the fused step kernels
+  size_t Wfrag;            // W_hh (forward) or its transpose (backward) of the layer being processed
+  size_t hF[2][2];         // h of the previous / next step, [slot][value, remainder]
+  size_t dGF[2][2];        // gate gradients of the next / this step
   int nrb;
   std::vector<GemmPlan> p_gx, p_dwi, p_dx;
   GemmPlan p_rec, p_drec, p_dwh;
@@ -195,20 +185,20 @@ LsLayout make_ls_layout(const ls_shape* s) {
     L.cs.push_back(take((size_t)(T + 1) * L.BH * 4));
     L.hE.push_back(take((size_t)(T + 1) * L.BH * L.e));
     L.out.push_back(l + 1 < NL ? take((size_t)TB * H * L.e) : 0);
-    L.hL.push_back(bf ? take((size_t)(T + 1) * L.BH * L.e) : 0);
     L.out_lo.push_back(bf && l + 1 < NL ? take((size_t)TB * H * L.e) : 0);
+    // bf16: the output of the layer below and the gate gradients are (value, remainder) pairs: two segments
     L.p_gx.push_back(gemm_plan(TB, 4 * H, (bf && l > 0) ? 2 * Il : Il, 1, bf, false));
     L.p_dwi.push_back(gemm_plan(4 * H, Il, TB, 1, bf, true));
     L.p_dx.push_back(gemm_plan(TB, Il, bf ? 8 * H : 4 * H, 1, bf, false));
     mx(gemm_partial_bytes(4 * H, Il, 1, L.p_dwi.back().splits));
   }
-  // bf16: the state / gate-gradient operand is a (value, remainder) pair: two segments, which only the
-  // 128x128 kernel can split
-  L.p_rec = gemm_plan(B, 4 * H, bf ? 2 * H : H, 1, bf, true, bf);
-  L.p_drec = gemm_plan(B, H, bf ? 8 * H : 4 * H, 1, bf, true, bf);
+  L.p_rec = gemm_plan(B, 4 * H, H, 1, false, true);      // the per-step products as launches of their own: fp32 only
+  L.p_drec = gemm_plan(B, H, 4 * H, 1, false, true);
   L.p_dwh = gemm_plan(4 * H, H, TB, 1, bf, true);
-  mx(gemm_partial_bytes(B, 4 * H, 1, L.p_rec.splits));
-  mx(gemm_partial_bytes(B, H, 1, L.p_drec.splits));
+  if (!bf) {
+    mx(gemm_partial_bytes(B, 4 * H, 1, L.p_rec.splits));
+    mx(gemm_partial_bytes(B, H, 1, L.p_drec.splits));
+  }
   mx(gemm_partial_bytes(4 * H, H, 1, L.p_dwh.splits));
   L.hf = take((size_t)L.BH * 4);
   L.dGE = take((size_t)TB * 4 * H * L.e);
@@ -221,6 +211,12 @@ LsLayout make_ls_layout(const ls_shape* s) {
   L.nrb = (TB + 63) / 64;
   L.dbpart = take((size_t)L.nrb * 4 * H * 4);
   L.partial = take(pb);
+  L.Wfrag = bf ? take((size_t)4 * H * H * L.e) : 0;
+  for (int sl = 0; sl < 2; ++sl)
+    for (int k = 0; k < 2; ++k) {
+      L.hF[sl][k] = bf ? take((size_t)L.BH * L.e) : 0;
+      L.dGF[sl][k] = bf ? take((size_t)4 * L.BH * L.e) : 0;
+    }
   L.total = off;
   return L;
 }
@@ -260,12 +256,11 @@ template <typename TE>
 as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int32_t* lengths,
                  const void* const* W_ih, const void* const* W_hh, const void* const* b, const float* h0,
                  const float* c0, char* y, float* hT, float* cT, char* w, hipStream_t st) {
-  const bool bf = sizeof(TE) == 2;
+  constexpr bool bf = sizeof(TE) == 2;
   const int T = s->T, B = s->B, I = s->I, H = s->H, NL = s->L;
   const int TB = (int)L.TB, BH = (int)L.BH;
   const int nb = (BH + 255) / 256;
   float* hf = reinterpret_cast<float*>(w + L.hf);
-  float* partial = reinterpret_cast<float*>(w + L.partial);
   const char* xin = x;
   const char* xin_lo = nullptr;   // the caller's x is exact in the storage type
   for (int l = 0; l < NL; ++l) {
@@ -274,10 +269,13 @@ as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     float* cs = reinterpret_cast<float*>(w + L.cs[l]);
     TE* hE = reinterpret_cast<TE*>(w + L.hE[l]);
     TE* out = reinterpret_cast<TE*>(l + 1 < NL ? w + L.out[l] : y);
-    TE* hL = bf ? reinterpret_cast<TE*>(w + L.hL[l]) : nullptr;
     TE* out_lo = (bf && l + 1 < NL) ? reinterpret_cast<TE*>(w + L.out_lo[l]) : nullptr;
+    TE* hF[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
+    if (bf)
+      for (int sl = 0; sl < 2; ++sl)
+        for (int k = 0; k < 2; ++k) hF[sl][k] = reinterpret_cast<TE*>(w + L.hF[sl][k]);
     hipLaunchKernelGGL(lstm_init_kernel<TE>, dim3(nb), dim3(256), 0, st, h0 ? h0 + (size_t)l * BH : nullptr,
-                       c0 ? c0 + (size_t)l * BH : nullptr, BH, hf, cs, hE, hL);
+                       c0 ? c0 + (size_t)l * BH : nullptr, B, H, hf, cs, hE, hF[0][0], hF[0][1]);
     LS_TRY(hipGetLastError());
     {  // input half of the pre-activations of all steps: X W_ih^T + b
       GemmArgs g;
@@ -288,23 +286,37 @@ as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
       g.C = gates; g.ldc = 4 * H; g.c_bf16 = false;
       LS_TRY(launch_gemm(g, bf, L.p_gx[l].big_tile, st));
     }
-    for (int t = 0; t < T; ++t) {
-      float* Gt = gates + (size_t)t * B * 4 * H;
-      {  // + h_{t-1} W_hh^T
-        GemmArgs g;
+    if constexpr (bf) {   // one kernel per step: recurrent product and cell
+      uint16_t* WF = reinterpret_cast<uint16_t*>(w + L.Wfrag);
+      LS_TRY(launch_ls_wfrag(W_hh[l], WF, H, false, st));
+      for (int t = 0; t < T; ++t) {
+        LstmStepFwd f;
+        f.WF = WF;
+        f.hF_hi = hF[t & 1][0]; f.hF_lo = hF[t & 1][1];
+        f.hFn_hi = hF[(t + 1) & 1][0]; f.hFn_lo = hF[(t + 1) & 1][1];
+        f.G = gates + (size_t)t * B * 4 * H;
+        f.c_prev = cs + (size_t)t * BH; f.c_new = cs + (size_t)(t + 1) * BH; f.hf = hf;
+        f.hE_new = hE + (size_t)(t + 1) * BH;
+        f.out = out + (size_t)t * BH; f.out_lo = out_lo ? out_lo + (size_t)t * BH : nullptr;
+        f.lengths = lengths; f.t = t; f.T = T; f.B = B; f.H = H;
+        LS_TRY(launch_lstm_step_fwd(f, st));
+      }
+    } else {              // fp32: the recurrent product and the cell as two launches per step
+      float* partial = reinterpret_cast<float*>(w + L.partial);
+      for (int t = 0; t < T; ++t) {
+        float* Gt = gates + (size_t)t * B * 4 * H;
+        GemmArgs g;       // + h_{t-1} W_hh^T
         g.seg(hE + (size_t)t * BH, H, 0, W_hh[l], H, 0, H);
-        if (hL) g.seg(hL + (size_t)t * BH, H, 0, W_hh[l], H, 0, H);
         g.a_kc = true; g.b_kc = true;
         g.M = B; g.N = 4 * H;
         g.C = Gt; g.ldc = 4 * H; g.c_bf16 = false; g.accumulate = 1;
         g.splits = L.p_rec.splits; g.partial = partial;
-        LS_TRY(launch_gemm(g, bf, L.p_rec.big_tile, st));
+        LS_TRY(launch_gemm(g, false, L.p_rec.big_tile, st));
+        hipLaunchKernelGGL(lstm_cell_fwd_kernel, dim3(nb), dim3(256), 0, st, Gt, cs + (size_t)t * BH,
+                           cs + (size_t)(t + 1) * BH, hf, hE + (size_t)t * BH, hE + (size_t)(t + 1) * BH,
+                           out + (size_t)t * BH, lengths, t, T, B, H);
+        LS_TRY(hipGetLastError());
       }
-      hipLaunchKernelGGL(lstm_cell_fwd_kernel<TE>, dim3(nb), dim3(256), 0, st, Gt, cs + (size_t)t * BH,
-                         cs + (size_t)(t + 1) * BH, hf, hE + (size_t)t * BH, hE + (size_t)(t + 1) * BH,
-                         hL ? hL + (size_t)t * BH : nullptr, hL ? hL + (size_t)(t + 1) * BH : nullptr,
-                         out + (size_t)t * BH, out_lo ? out_lo + (size_t)t * BH : nullptr, lengths, t, T, B, H);
-      LS_TRY(hipGetLastError());
     }
     if (hT) LS_TRY(hipMemcpyAsync(hT + (size_t)l * BH, hf, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
     if (cT) LS_TRY(hipMemcpyAsync(cT + (size_t)l * BH, cs + (size_t)T * BH, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
@@ -319,7 +331,7 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
                  const void* const* W_ih, const void* const* W_hh, const float* dy, const float* dhT,
                  const float* dcT, char* w, float* dx, float* const* dW_ih, float* const* dW_hh, float* const* db,
                  float* dh0, float* dc0, hipStream_t st) {
-  const bool bf = sizeof(TE) == 2;
+  constexpr bool bf = sizeof(TE) == 2;
   const int T = s->T, B = s->B, I = s->I, H = s->H, NL = s->L;
   const int TB = (int)L.TB, BH = (int)L.BH;
   const int nb = (BH + 255) / 256;
@@ -336,25 +348,51 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     const float* cs = reinterpret_cast<const float*>(w + L.cs[l]);
     const TE* hE = reinterpret_cast<const TE*>(w + L.hE[l]);
     const char* xin = l == 0 ? x : w + L.out[l - 1];
-    hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dhT ? dhT + (size_t)l * BH : nullptr, dhs, BH);
+    const float* dhT_l = dhT ? dhT + (size_t)l * BH : nullptr;
     hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dcT ? dcT + (size_t)l * BH : nullptr, dcs, BH);
     LS_TRY(hipGetLastError());
-    for (int t = T - 1; t >= 0; --t) {
-      TE* dGt = dGE + (size_t)t * B * 4 * H;
-      TE* dGlt = dGlo ? dGlo + (size_t)t * B * 4 * H : nullptr;
-      hipLaunchKernelGGL(lstm_cell_bwd_kernel<TE>, dim3(nb), dim3(256), 0, st, gates + (size_t)t * B * 4 * H,
-                         cs + (size_t)t * BH, cs + (size_t)(t + 1) * BH, dout + (size_t)t * BH, dhs, dcs, dGt, dGlt,
-                         lengths, t, T, B, H);
+    if constexpr (bf) {   // one kernel per step: da_{t+1} W_hh and the cell derivative of step t
+      uint16_t* WTF = reinterpret_cast<uint16_t*>(w + L.Wfrag);
+      LS_TRY(launch_ls_wfrag(W_hh[l], WTF, H, true, st));
+      uint16_t* dGF[2][2];
+      for (int sl = 0; sl < 2; ++sl)
+        for (int k = 0; k < 2; ++k) dGF[sl][k] = reinterpret_cast<uint16_t*>(w + L.dGF[sl][k]);
+      for (int t = T - 1; t >= -1; --t) {   // t = -1: the product alone, for the gradient of the initial h
+        LstmStepBwd q;
+        q.WTF = WTF;
+        q.dGnF_hi = t + 1 < T ? dGF[(t + 1) & 1][0] : nullptr;
+        q.dGnF_lo = t + 1 < T ? dGF[(t + 1) & 1][1] : nullptr;
+        q.dhT = dhT_l;
+        q.dcs = dcs;
+        q.lengths = lengths; q.t = t; q.T = T; q.B = B; q.H = H;
+        q.gates = nullptr; q.c_prev = q.c_new = q.dout_t = nullptr;
+        q.dG_hi = q.dG_lo = q.dGF_hi = q.dGF_lo = nullptr;
+        q.dh0_out = dhs;
+        if (t >= 0) {
+          q.gates = gates + (size_t)t * B * 4 * H;
+          q.c_prev = cs + (size_t)t * BH; q.c_new = cs + (size_t)(t + 1) * BH;
+          q.dout_t = dout + (size_t)t * BH;
+          q.dG_hi = dGE + (size_t)t * B * 4 * H; q.dG_lo = dGlo + (size_t)t * B * 4 * H;
+          q.dGF_hi = dGF[t & 1][0]; q.dGF_lo = dGF[t & 1][1];
+        }
+        LS_TRY(launch_lstm_step_bwd(q, st));
+      }
+    } else {              // fp32: cell derivative and product as two launches per step
+      hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dhT_l, dhs, BH);
       LS_TRY(hipGetLastError());
-      {  // dh_{t-1} (+)= da_t W_hh: valid rows were cleared, padded rows have da_t = 0 and keep theirs
-        GemmArgs g;
+      for (int t = T - 1; t >= 0; --t) {
+        float* dGt = dGE + (size_t)t * B * 4 * H;
+        hipLaunchKernelGGL(lstm_cell_bwd_kernel, dim3(nb), dim3(256), 0, st, gates + (size_t)t * B * 4 * H,
+                           cs + (size_t)t * BH, cs + (size_t)(t + 1) * BH, dout + (size_t)t * BH, dhs, dcs, dGt, lengths,
+                           t, T, B, H);
+        LS_TRY(hipGetLastError());
+        GemmArgs g;       // dh_{t-1} (+)= da_t W_hh: valid rows were cleared, padded rows have da_t = 0 and keep theirs
         g.seg(dGt, 4 * H, 0, W_hh[l], H, 0, 4 * H);
-        if (dGlt) g.seg(dGlt, 4 * H, 0, W_hh[l], H, 0, 4 * H);
         g.a_kc = true; g.b_kc = false;
         g.M = B; g.N = H;
         g.C = dhs; g.ldc = H; g.c_bf16 = false; g.accumulate = 1;
         g.splits = L.p_drec.splits; g.partial = partial;
-        LS_TRY(launch_gemm(g, bf, L.p_drec.big_tile, st));
+        LS_TRY(launch_gemm(g, false, L.p_drec.big_tile, st));
       }
     }
     {  // dW_hh = sum_t da_t^T h_{t-1}
@@ -395,7 +433,6 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
   }
   return AS_OK;
 }
-
 }  // namespace
 }  // namespace asx
 
