@@ -54,42 +54,61 @@ __device__ __forceinline__ int ls_len(const int32_t* lengths, int b, int T) {
 }
 
 // ---- forward ---------------------------------------------------------------------
-// Block: 64 gate rows (16 hidden units x 4 gates) x 64 sentences, 4 waves splitting the reduction over H.
+// Block: 64 gate rows (16 hidden units x 4 gates) x 32*LSF_NJ sentences, LSF_KS waves splitting the reduction over H.
 // MFMA row rho of a 32-row tile that starts at unit u: unit u + 4*((rho >> 2) & 1) + (rho >> 3), gate rho & 3,
 // i.e. weight row gate*H + unit; output register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, so the lane
 // holds units u + 4*(l/32) + r/4 (r/4 = 0..3), gate r%4.
-constexpr int LSF_KS = 4;
-constexpr int LSF_U = 8;     // reduction steps whose loads are in flight together (6 x 16 bytes per lane each)
-constexpr int LSF_SMEM = LSF_KS * 64 * 64 * 4;
+constexpr int LSF_NJ = 1;    // 32-sentence column tiles per block
+constexpr int LSF_KS = 8;    // waves per block = ways the reduction is split
+constexpr int LSF_U = 8;     // reduction steps whose loads are in flight together
+constexpr int LSF_SMEM = LSF_KS * 2 * LSF_NJ * 16 * 64 * 4;
+static_assert(2 * LSF_NJ <= LSF_KS, "one wave per output tile finishes it");
 
 __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd p) {
+  constexpr int NJ = LSF_NJ;
   extern __shared__ float red[];   // [wave][tile*16 + r][lane]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rho = lane & 31, kq = lane >> 5;
-  const int u0 = blockIdx.x * 16, b0 = blockIdx.y * 64;
+  const int u0 = blockIdx.x * 16, b0 = blockIdx.y * 32 * NJ;
   const int H = p.H, B = p.B;
 
   // element offsets inside one 8-wide reduction chunk of the fragment-major operands
-  int64_t woff[2], hoff[2];
-  bool wok[2], bok[2];
+  int64_t woff[2], hoff[NJ];
+  bool wok[2], bok[NJ];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {   // WF rows are ordered unit*4 + gate: the 32 rows of a tile are contiguous
     wok[i] = u0 + 8 * i < H;      // H % 8 == 0: a tile of 8 units is all inside or all outside
     woff[i] = ((int64_t)(u0 + 8 * i) * 4 + 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3)) * 8;
   }
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < NJ; ++j) {
     const int b = b0 + 32 * j + rho;
     bok[j] = b < B;
     hoff[j] = (int64_t)(bok[j] ? b : 0) * 8;
   }
   const int64_t wchunk = (int64_t)4 * H * 8, hchunk = (int64_t)B * 8;   // elements per chunk of WF / hF
   const int nchunks = H / 8;
-  f32x16_t acc[2][2];
+
+  // What the wave that finishes an output tile needs from memory is requested now, ahead of the product:
+  // the step is a chain of memory latencies, and this one would otherwise sit at its very end.
+  constexpr int NT = 2 * NJ;   // output tiles of the block; wave w < NT finishes tile w = (i, j)
+  const int ti = wave / NJ, tj = wave % NJ;
+  const int b = b0 + 32 * tj + rho;
+  const int unit0 = u0 + 8 * ti + 4 * kq;   // this lane: units unit0 .. unit0 + 3 (H % 4 == 0: all in or all out)
+  const bool fin = wave < NT && b < B && unit0 < H;
+  const int64_t idx = (int64_t)(fin ? b : 0) * H + (fin ? unit0 : 0);
+  float* Gp = p.G + (int64_t)(fin ? b : 0) * 4 * H + (fin ? unit0 : 0);
+  f32x4_t gx[4], cp;
+  if (fin) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) gx[g] = *reinterpret_cast<const f32x4_t*>(Gp + (int64_t)g * H);
+    cp = *reinterpret_cast<const f32x4_t*>(p.c_prev + idx);
+  }
+  f32x16_t acc[2][NJ];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -97,7 +116,7 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
   // the fragments of LSF_U reduction steps are requested before the first of them is used.
   const int nks = (H + 15) / 16;
   for (int ks0 = wave; ks0 < nks; ks0 += LSF_KS * LSF_U) {
-    bf16x8_t wf[LSF_U][2], hf[LSF_U][2], lf[LSF_U][2];
+    bf16x8_t wf[LSF_U][2], hf[LSF_U][NJ], lf[LSF_U][NJ];
 #pragma unroll
     for (int u = 0; u < LSF_U; ++u) {
       const int kc = (ks0 + u * LSF_KS) * 2 + kq;   // this lane's chunk of the 16-wide step
@@ -105,7 +124,7 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
 #pragma unroll
       for (int i = 0; i < 2; ++i) wf[u][i] = ls_frag(p.WF + kc * wchunk + woff[i], kin && wok[i]);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NJ; ++j) {
         hf[u][j] = ls_frag(p.hF_hi + kc * hchunk + hoff[j], kin && bok[j]);
         lf[u][j] = ls_frag(p.hF_lo + kc * hchunk + hoff[j], kin && bok[j]);
       }
@@ -115,7 +134,7 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NJ; ++j) {
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u][i], hf[u][j], acc[i][j], 0, 0, 0);
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[u][i], lf[u][j], acc[i][j], 0, 0, 0);
         }
@@ -123,31 +142,22 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) red[((wave * 4 + i * 2 + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+      for (int r = 0; r < 16; ++r) red[((wave * NT + i * NJ + j) * 16 + r) * 64 + lane] = acc[i][j][r];
   __syncthreads();
+  if (!fin) return;
 
-  // wave w finishes tile w = (i, j): partial sums added in wave order
-  const int ti = wave >> 1, tj = wave & 1;
+  // partial sums added in wave order
   float v[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     float s = 0.f;
 #pragma unroll
-    for (int w = 0; w < LSF_KS; ++w) s += red[((w * 4 + wave) * 16 + r) * 64 + lane];
+    for (int w = 0; w < LSF_KS; ++w) s += red[((w * NT + wave) * 16 + r) * 64 + lane];
     v[r] = s;
   }
-  const int b = b0 + 32 * tj + rho;
-  const int unit0 = u0 + 8 * ti + 4 * kq;   // this lane: units unit0 .. unit0 + 3 (H % 4 == 0: all in or all out)
-  if (b >= B || unit0 >= H) return;
   const bool valid = p.t < ls_len(p.lengths, b, p.T);
-  float* Gp = p.G + (int64_t)b * 4 * H + unit0;
-  const int64_t idx = (int64_t)b * H + unit0;
-  f32x4_t gx[4];
-#pragma unroll
-  for (int g = 0; g < 4; ++g) gx[g] = *reinterpret_cast<const f32x4_t*>(Gp + (int64_t)g * H);
-  const f32x4_t cp = *reinterpret_cast<const f32x4_t*>(p.c_prev + idx);
   f32x4_t gi, gf, gg, go, cn;
   float hn[4];
 #pragma unroll
@@ -187,13 +197,13 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
 }
 
 // ---- backward --------------------------------------------------------------------
-// Block: 32 hidden units x 32 sentences, 16 waves splitting the reduction over the 4H gate rows of step t+1:
+// Block: 32 hidden units x 32 sentences, 8 waves splitting the reduction over the 4H gate rows of step t+1:
 // rec[b,u] = sum_n da_{t+1}[b,n] W_hh[n,u] (weights read from the transposed copy WT [H,4H]).  The gradient
 // w.r.t. h_t is rec where step t+1 was a word of sentence b, else the gradient that came in for the final
 // state (sentences are right-padded, so the steps of a sentence are a prefix).  Then the cell derivative of
 // step t.  t = -1: only the product, written out as the gradient of the initial state.
-constexpr int LSB_KS = 16;
-constexpr int LSB_U = 4;     // 16 waves per block leave 128 registers per lane: 4 steps x 3 fragments in flight
+constexpr int LSB_KS = 8;
+constexpr int LSB_U = 8;     // reduction steps whose loads are in flight together (3 fragments each)
 constexpr int LSB_SMEM = LSB_KS * 16 * 64 * 4;
 
 __global__ __launch_bounds__(64 * LSB_KS) void lstm_step_bwd_kernel(LstmStepBwd p) {
@@ -202,6 +212,27 @@ __global__ __launch_bounds__(64 * LSB_KS) void lstm_step_bwd_kernel(LstmStepBwd 
   const int rho = lane & 31, kq = lane >> 5;
   const int u0 = blockIdx.x * 32, b0 = blockIdx.y * 32;
   const int H = p.H, B = p.B, K = 4 * p.H;
+
+  // the inputs of the cell derivative are requested ahead of the product (waves 0..3 finish the tile)
+  const int b = b0 + rho;
+  const int unit0 = u0 + 8 * (wave & 3) + 4 * kq;
+  const bool fin = wave < 4 && b < B && unit0 < H;
+  const int64_t idx = (int64_t)(fin ? b : 0) * H + (fin ? unit0 : 0);
+  const int len = fin ? ls_len(p.lengths, b, p.T) : 0;
+  const bool cell = fin && p.t >= 0 && p.t < len;
+  f32x4_t gi, gf, gg, go, cp, cn, dy, dcs, carried = {0.f, 0.f, 0.f, 0.f};
+  if (fin && p.dhT) carried = *reinterpret_cast<const f32x4_t*>(p.dhT + idx);
+  if (cell) {
+    const float* Gp = p.gates + (int64_t)b * K + unit0;
+    gi = *reinterpret_cast<const f32x4_t*>(Gp);
+    gf = *reinterpret_cast<const f32x4_t*>(Gp + (int64_t)H);
+    gg = *reinterpret_cast<const f32x4_t*>(Gp + 2 * (int64_t)H);
+    go = *reinterpret_cast<const f32x4_t*>(Gp + 3 * (int64_t)H);
+    cp = *reinterpret_cast<const f32x4_t*>(p.c_prev + idx);
+    cn = *reinterpret_cast<const f32x4_t*>(p.c_new + idx);
+    dy = *reinterpret_cast<const f32x4_t*>(p.dout_t + idx);
+    dcs = *reinterpret_cast<const f32x4_t*>(p.dcs + idx);
+  }
 
   f32x16_t acc;
 #pragma unroll
@@ -233,7 +264,7 @@ __global__ __launch_bounds__(64 * LSB_KS) void lstm_step_bwd_kernel(LstmStepBwd 
 #pragma unroll
   for (int r = 0; r < 16; ++r) red[(wave * 16 + r) * 64 + lane] = acc[r];
   __syncthreads();
-  if (wave >= 4) return;          // waves 0..3 finish four consecutive units each (register group r/4 = wave)
+  if (!fin) return;               // waves 0..3 finish four consecutive units each (register group r/4 = wave)
   float rec[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -242,35 +273,17 @@ __global__ __launch_bounds__(64 * LSB_KS) void lstm_step_bwd_kernel(LstmStepBwd 
     for (int w = 0; w < LSB_KS; ++w) s += red[(w * 16 + 4 * wave + e) * 64 + lane];
     rec[e] = s;
   }
-  const int b = b0 + rho;
-  const int unit0 = u0 + 8 * wave + 4 * kq;
-  if (b >= B || unit0 >= H) return;
-  const int len = ls_len(p.lengths, b, p.T);
   const bool valid_next = p.t + 1 < len;
-  const int64_t idx = (int64_t)b * H + unit0;
   f32x4_t dh;
-  {
-    f32x4_t carried = {0.f, 0.f, 0.f, 0.f};
-    if (p.dhT) carried = *reinterpret_cast<const f32x4_t*>(p.dhT + idx);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) dh[e] = valid_next ? rec[e] : carried[e];
-  }
+  for (int e = 0; e < 4; ++e) dh[e] = valid_next ? rec[e] : carried[e];
   if (p.t < 0) {
     *reinterpret_cast<f32x4_t*>(p.dh0_out + idx) = dh;
     return;
   }
   uint16_t* dhi = p.dG_hi + (int64_t)b * K + unit0;
   uint16_t* dlo = p.dG_lo + (int64_t)b * K + unit0;
-  if (p.t < len) {
-    const float* Gp = p.gates + (int64_t)b * K + unit0;
-    const f32x4_t gi = *reinterpret_cast<const f32x4_t*>(Gp);
-    const f32x4_t gf = *reinterpret_cast<const f32x4_t*>(Gp + (int64_t)H);
-    const f32x4_t gg = *reinterpret_cast<const f32x4_t*>(Gp + 2 * (int64_t)H);
-    const f32x4_t go = *reinterpret_cast<const f32x4_t*>(Gp + 3 * (int64_t)H);
-    const f32x4_t cp = *reinterpret_cast<const f32x4_t*>(p.c_prev + idx);
-    const f32x4_t cn = *reinterpret_cast<const f32x4_t*>(p.c_new + idx);
-    const f32x4_t dy = *reinterpret_cast<const f32x4_t*>(p.dout_t + idx);
-    f32x4_t dcs = *reinterpret_cast<const f32x4_t*>(p.dcs + idx);
+  if (cell) {
     float da[4][4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -344,7 +357,7 @@ hipError_t launch_lstm_step_fwd(const LstmStepFwd& p, hipStream_t st) {
     attr_set = true;
   }
   if ((p.H & 7) != 0 || p.B < 1) return hipErrorInvalidValue;
-  dim3 grid((p.H + 15) / 16, (p.B + 63) / 64);
+  dim3 grid((p.H + 15) / 16, (p.B + 32 * LSF_NJ - 1) / (32 * LSF_NJ));
   hipLaunchKernelGGL(lstm_step_fwd_kernel, grid, dim3(64 * LSF_KS), LSF_SMEM, st, p);
   return hipGetLastError();
 }
