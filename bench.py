@@ -26,6 +26,10 @@ adam       = the fused Adam update of the four parameter tensors (outside the ti
              or 32 (f32) against the HBM peak
 per_step   = the per-step mode (T = 1) at the paper's model size, outside the timed steps: microseconds
              per decoder step of attn_softmax_fwd called with T = 1 and of attn_softmax_step_fwd
+lstm_stack = the stacked-LSTM part that produces the hidden states (lstm_stack_fwd / lstm_stack_bwd), outside
+             the timed steps, at the paper's model size (Table 2: embedding 512, hidden 1024, depth 4; B = 128,
+             50 steps per side): encoder forward, decoder forward from the encoder's final states, decoder
+             backward, encoder backward; per-step kernel time against the bytes a step must move
 --train-step makes a step = forward with dropout 0.3 + backward + Adam on the four
              parameter tensors (the headline metric stays forward + backward)
 """
@@ -130,6 +134,62 @@ def per_step_probe(lib, torch, B=128, S=50, H=1024, V=32000, iters=200):
             "us_step_fwd": us_step, "bound": "hbm", "bytes_per_step": bytes_step,
             "achieved": bytes_step / (us_step * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": bytes_step / (us_step * 1e-6) / 1e9 / PEAK_HBM_GBS}
+
+
+def lstm_probe(lib, torch, T=50, B=128, I=512, H=1024, L=4, iters=5):
+    """Encoder + decoder of the proposed model without input feeding (section 3.2, Fig. 3) at Table 2's size:
+    ms per training step of the LSTM part and of its pieces, source+target tokens per second, the average
+    duration of one time step of one layer (forward / backward kernel), and that step's algorithmic bytes
+    (W_hh, h as value + remainder, the input half of the pre-activations read, gates + c + h written; backward:
+    W_hh, gate gradients of the next step as value + remainder, saved gates and cell states read, gate gradients
+    written twice) against the HBM peak."""
+    from synth_inputs import make_lstm_inputs
+    enc_in = make_lstm_inputs(T, B, I, H, L, seed=50, dtype="bf16", min_len=20)
+    dec_in = make_lstm_inputs(T, B, I, H, L, seed=51, dtype="bf16", min_len=20)
+    enc = lib.DeviceLstm(enc_in.x, enc_in.lengths, enc_in.W_ih, enc_in.W_hh, enc_in.b, dtype="bf16")
+    dec = lib.DeviceLstm(dec_in.x, dec_in.lengths, dec_in.W_ih, dec_in.W_hh, dec_in.b, dtype="bf16")
+    dec.h0, dec.c0 = enc.hT, enc.cT                           # the decoder starts from the encoder's final states
+    dy_dec = torch.from_numpy(dec_in.dy).to(enc.dev)          # stand-ins for d_h_dec / d_h_enc of the attention part
+    dy_enc = torch.from_numpy(enc_in.dy).to(enc.dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def run(timed):
+        marks = [ev() for _ in range(5)]
+        marks[0].record(); enc.fwd()
+        marks[1].record(); dec.fwd()
+        marks[2].record(); dec.bwd(dy_dec)
+        marks[3].record(); enc.bwd(dy_enc, dec.dh0, dec.dc0)
+        marks[4].record()
+        if timed:
+            enc.sync()
+            return [marks[i].elapsed_time(marks[i + 1]) for i in range(4)]
+        return None
+
+    for _ in range(2):
+        run(False)
+    enc.sync()
+    acc = [0.0] * 4
+    for _ in range(iters):
+        for i, v in enumerate(run(True)):
+            acc[i] += v / iters
+    total = sum(acc)
+    tokens = int(enc_in.lengths.sum() + dec_in.lengths.sum())
+    # one layer-step: the fused kernel's share of a forward / backward call (the large products over all steps
+    # are a minor part; the per-kernel figure is in profiles/)
+    e = 2
+    fwd_bytes = 4 * H * H * e + 2 * B * H * e + B * 4 * H * 4 * 2 + B * H * (4 + 4 + 2 * 4)
+    bwd_bytes = 4 * H * H * e + 2 * B * 4 * H * e + B * 4 * H * 4 + B * H * 4 * 5 + 4 * B * 4 * H * e
+    us_f = acc[0] / (T * L) * 1e3
+    us_b = acc[3] / (T * L) * 1e3
+    return {"workload": f"encoder+decoder T={T} B={B} I={I} H={H} L={L} bf16, no input feeding",
+            "ms_enc_fwd": acc[0], "ms_dec_fwd": acc[1], "ms_dec_bwd": acc[2], "ms_enc_bwd": acc[3], "ms_total": total,
+            "src_plus_tgt_tokens_per_sec": tokens / (total * 1e-3), "tokens": tokens,
+            "us_per_layer_step_fwd": us_f, "us_per_layer_step_bwd": us_b,
+            "bound": "hbm", "bytes_per_layer_step_fwd": fwd_bytes, "bytes_per_layer_step_bwd": bwd_bytes,
+            "achieved": fwd_bytes / (us_f * 1e-6) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": fwd_bytes / (us_f * 1e-6) / 1e9 / PEAK_HBM_GBS}
 
 
 def main():
@@ -292,6 +352,7 @@ def main():
     del db
     torch.cuda.empty_cache()
     out["per_step"] = per_step_probe(lib, torch)
+    out["lstm_stack"] = lstm_probe(lib, torch)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(out))
