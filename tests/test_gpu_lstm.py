@@ -110,3 +110,94 @@ def test_lstm_paper_size_sixteen_sentences():
     log = {}
     compare(inp, f, g, fo, go, log)
     print({k: (round(v["ratio"], 3), float(f"{v['norm']:.2e}")) for k, v in log.items()})
+
+
+def test_lstm_paper_size_full_batch_sampled():
+    """The configuration bench.py times (B = 128 at Table 2's size).  Sentences are independent in everything
+    but the weight gradients: y, the final states, dx and the initial-state gradients of 6 sampled sentences
+    are compared with the oracle run on those sentences alone; the weight gradients of the batch must equal the
+    sum over 4 shards (fp32 summation order only)."""
+    T, B, I, H, L = 50, 128, 512, 1024, 4
+    inp = make_lstm_inputs(T, B, I, H, L, seed=50, dtype="bf16", min_len=20)
+    f, g, _ = run_gpu(inp)
+    idx = [0, 17, 63, 64, 101, 127]
+
+    def take(a, axis):
+        return np.ascontiguousarray(np.take(a, idx, axis=axis))
+
+    sub = make_lstm_inputs(T, B, I, H, L, seed=50, dtype="bf16", min_len=20)
+    sub.B = len(idx)
+    sub.x, sub.lengths, sub.dy = take(inp.x, 1), take(inp.lengths, 0), take(inp.dy, 1)
+    sub.h0, sub.c0, sub.dhT, sub.dcT = take(inp.h0, 1), take(inp.c0, 1), take(inp.dhT, 1), take(inp.dcT, 1)
+    fo, go = run_oracle(sub)
+    valid = fo["valid"]
+    assert np.all(f["y"][:, idx][~valid] == 0.0)
+    for k in ("y", "hT", "cT"):
+        pu.assert_close(f[k][:, idx], fo[k], "bf16", k)
+    for k in ("dx", "dh0", "dc0"):
+        pu.assert_close(g[k][:, idx], go[k], "bf16", k)
+    acc = {k: [np.zeros_like(a, dtype=np.float64) for a in g[k]] for k in ("dW_ih", "dW_hh", "db")}
+    q = B // 4
+    for i in range(4):
+        sl = slice(i * q, (i + 1) * q)
+        sh = make_lstm_inputs(T, B, I, H, L, seed=50, dtype="bf16", min_len=20)
+        sh.B = q
+        sh.x, sh.lengths, sh.dy = inp.x[:, sl].copy(), inp.lengths[sl].copy(), inp.dy[:, sl].copy()
+        sh.h0, sh.c0, sh.dhT, sh.dcT = (a[:, sl].copy() for a in (inp.h0, inp.c0, inp.dhT, inp.dcT))
+        fs, gs, _ = run_gpu(sh)
+        assert np.array_equal(fs["y"], f["y"][:, sl])           # a sentence does not see the batch around it
+        for k in acc:
+            for l in range(L):
+                acc[k][l] += gs[k][l]
+    for k in acc:
+        for l in range(L):
+            s = pu.err_stats(acc[k][l], g[k][l], "bf16")
+            assert s["norm"] <= 5e-4, (k, l, s)
+
+
+def test_encoder_decoder_attention_chain_fp32():
+    """The interfaces fit: encoder LSTM -> decoder LSTM (initial state = the encoder's final state) ->
+    attention-softmax forward/backward -> decoder backward -> encoder backward (which also receives the
+    gradient of the decoder's initial state), fp32 storage, against the two oracles chained the same way."""
+    import torch
+    import paper_1909_00562_amd as lib
+    from oracle import attn_softmax_oracle as orc
+    from synth_inputs import make_custom
+    S, T, B, I, H, L, V = 7, 6, 4, 12, 16, 2, 53
+    enc_in = make_lstm_inputs(S, B, I, H, L, seed=31, dtype="f32")
+    dec_in = make_lstm_inputs(T, B, I, H, L, seed=32, dtype="f32")
+    att = make_custom(T=T, S=S, B=B, H=H, V=V, seed=33, dtype="f32", min_len=1)
+    att.src_len = enc_in.lengths.copy()
+    for b in range(B):                       # targets are padding exactly where the decoder's sentence has ended
+        att.targets[:, b] = np.where(np.arange(T) < dec_in.lengths[b], np.maximum(att.targets[:, b], 1), att.pad_id)
+
+    # oracle chain
+    eo = lo.forward(enc_in.x, enc_in.lengths, enc_in.W_ih, enc_in.W_hh, enc_in.b)
+    do = lo.forward(dec_in.x, dec_in.lengths, dec_in.W_ih, dec_in.W_hh, dec_in.b, eo["hT"], eo["cT"])
+    args = (do["y"], eo["y"], att.src_len, att.W_a, att.W_c, att.W_out, att.b_out, att.targets, att.pad_id)
+    fo = orc.forward(*args)
+    go = orc.backward(*args, grad_scale=1.0)
+    dgo = lo.backward(do, go["d_h_dec"])
+    ego = lo.backward(eo, go["d_h_enc"], dgo["dh0"], dgo["dc0"])
+
+    # GPU chain: device tensors handed from one entry point to the next
+    enc = lib.DeviceLstm(enc_in.x, enc_in.lengths, enc_in.W_ih, enc_in.W_hh, enc_in.b, dtype="f32")
+    dec = lib.DeviceLstm(dec_in.x, dec_in.lengths, dec_in.W_ih, dec_in.W_hh, dec_in.b, dtype="f32")
+    enc.fwd()
+    dec.h0, dec.c0 = enc.hT, enc.cT
+    dec.fwd()
+    db = lib.DeviceBatch(att)
+    db.h_dec, db.h_enc = dec.y, enc.y
+    db.fwd()
+    db.bwd()
+    dec.bwd(db.d_h_dec)
+    enc.bwd(db.d_h_enc, dec.dh0, dec.dc0)
+    enc.sync()
+    assert int(db.n_tok.item()) == fo["n_tok"]
+    assert abs(float(db.loss_sum.item()) - fo["loss_sum"]) <= 1e-4 * abs(fo["loss_sum"])
+    pu.assert_close(_host(dec.dx), dgo["dx"], "f32", "decoder dx")
+    pu.assert_close(_host(enc.dx), ego["dx"], "f32", "encoder dx")
+    for l in range(L):
+        pu.assert_close(_host(dec.dW_hh[l]), dgo["dW_hh"][l], "f32", f"decoder dW_hh[{l}]")
+        pu.assert_close(_host(enc.dW_ih[l]), ego["dW_ih"][l], "f32", f"encoder dW_ih[{l}]")
+        pu.assert_close(_host(enc.db[l]), ego["db"][l], "f32", f"encoder db[{l}]")
