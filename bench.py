@@ -24,6 +24,8 @@ cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
 adam       = the fused Adam update of the four parameter tensors (outside the timed
              steps unless --train-step): 30 bytes per element (bf16 storage copy)
              or 32 (f32) against the HBM peak
+ms_per_step_hip_graph_replay = the same forward + backward captured once into a HIP graph and replayed (the
+             headline value is the eager one)
 per_step   = the per-step mode (T = 1) at the paper's model size, outside the timed steps: microseconds
              per decoder step of attn_softmax_fwd called with T = 1 and of attn_softmax_step_fwd
 lstm_stack = the stacked-LSTM part that produces the hidden states (lstm_stack_fwd / lstm_stack_bwd), outside
@@ -282,6 +284,25 @@ def main():
     lib.attn_softmax_profile_enable(False)
     assert int(db.n_tok.item()) == n_tok
 
+    # the same step replayed from a HIP graph (one capture of forward + backward): what the launches cost
+    graph_ms = None
+    if not a.train_step:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        db.sync()
+        with torch.cuda.graph(graph, stream=side):
+            db.fwd()
+            db.bwd()
+        graph.replay()
+        db.sync()
+        g0 = time.perf_counter()
+        for _ in range(a.steps):
+            graph.replay()
+        db.sync()
+        graph_ms = (time.perf_counter() - g0) / a.steps * 1e3
+        assert int(db.n_tok.item()) == n_tok
+        del graph
+
     # the Adam update on its own (gradients of the last step), HIP events on the launch stream
     adam(); db.sync()
     lib.attn_softmax_profile_enable(True)
@@ -347,6 +368,7 @@ def main():
                  "peak": PEAK_HBM_GBS, "unit": "GB/s",
                  "frac": adam_bytes / (adam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if adam_ms > 0 else 0.0},
         "step_is": "fwd(dropout 0.3)+bwd+adam" if a.train_step else "fwd+bwd",
+        "ms_per_step_hip_graph_replay": graph_ms,
     }
     del adam_state
     del db

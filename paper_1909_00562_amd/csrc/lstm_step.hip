@@ -9,7 +9,7 @@
 //     coalesced both operands are kept FRAGMENT-MAJOR, [K/8][rows][8]: the 32 lanes
 //     that hold the 32 rows of a fragment read 512 contiguous bytes (a row-major
 //     operand would make every lane touch a cache line of its own: measured 20 us
-//     per step against 5).  The weights are put into that form once per call and
+//     per forward step against 13 with nothing else changed).  The weights are put into that form once per call and
 //     layer; the state and the gate gradients are written in it by the step before;
 //   * the reduction is split over the waves of a block (interleaved 16-wide steps, so
 //     neighbouring waves read neighbouring 32-byte pieces of the same cache lines) and

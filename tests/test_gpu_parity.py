@@ -305,3 +305,32 @@ def test_full_size_config_sampled(name, skip):
         assert s["norm"] <= 5e-4, (k, s)
     rel = float((acc_out - dW_out_full).norm() / dW_out_full.norm())
     assert rel <= 5e-4, rel
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@SKIP
+def test_forward_backward_replays_from_a_hip_graph(skip):
+    """The entry points only enqueue on the caller's stream (no allocation, no synchronisation, no host
+    read-back), so a forward+backward pair can be captured into a HIP graph.  Every replay, with eager work and
+    synchronisations of the program in between, must reproduce the eager result bit for bit."""
+    import torch
+    inp = make_inputs("small", dtype="bf16")
+    run = pu.GpuRun(inp, skip_pad_rows=skip)
+    f0, g0 = run.fwd(), run.bwd()                     # eager reference (also warms every kernel up)
+    db = run.db
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        db.fwd()
+        db.bwd()
+    for rep in range(3):
+        for t in (db.loss_sum, db.dW_out, db.dW_a, db.d_h_dec, db.d_h_enc, db.db_out):
+            t.zero_()                                 # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert float(db.loss_sum.item()) == f0["loss_sum"], rep
+        assert int(db.n_tok.item()) == f0["n_tok"]
+        for k in ("d_h_dec", "d_h_enc", "dW_a", "dW_c", "dW_out", "db_out"):
+            assert np.array_equal(pu._host(getattr(db, k)), g0[k]), (k, rep)
