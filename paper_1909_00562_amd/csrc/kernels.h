@@ -79,18 +79,18 @@ struct LstmStepFwd {
   int t, T, B, H;
 };
 hipError_t launch_lstm_step_fwd(const LstmStepFwd& p, hipStream_t st);
-// Backward of step t: WTF = W_hh^T [H,4H] fragment-major (launch_ls_wfrag, backward); dGnF_hi / dGnF_lo: gate
-// gradients of step t+1 [B,4H] fragment-major (null for t = T-1); gates [B,4H], c_prev, c_new [B,H] as saved by
+// Backward of step t: WTF = W_hh^T [H,4H] fragment-major (launch_ls_wfrag, backward); dGnF: gate gradients
+// of step t+1 [B,4H] fragment-major, bf16 value only (null for t = T-1); gates [B,4H], c_prev, c_new [B,H] as saved by
 // the forward step; dout_t [B,H] gradient w.r.t. the layer's output; dhT [B,H] gradient w.r.t. the final h
 // (null = 0); dcs [B,H] running gradient w.r.t. c (in: after step t, out: after step t-1); gate gradients of
-// step t: dG_hi / dG_lo [B,4H] row-major and dGF_hi / dGF_lo fragment-major.
+// step t: dG_hi / dG_lo [B,4H] row-major (value, remainder) and dGF fragment-major (value).
 // t = -1: dh0_out [B,H] = gradient w.r.t. the initial h, nothing else is touched.
 struct LstmStepBwd {
   const uint16_t* WTF;
-  const uint16_t *dGnF_hi, *dGnF_lo;
+  const uint16_t* dGnF;
   const float *gates, *c_prev, *c_new, *dout_t, *dhT;
   float* dcs;
-  uint16_t *dG_hi, *dG_lo, *dGF_hi, *dGF_lo;
+  uint16_t *dG_hi, *dG_lo, *dGF;
   float* dh0_out;
   const int32_t* lengths;
   int t, T, B, H;

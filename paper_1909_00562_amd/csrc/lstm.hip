@@ -118,20 +118,37 @@ __global__ __launch_bounds__(256) void lstm_copy_or_zero_kernel(const float* __r
 
 // column sums of da [rows, cols] (+ its rounding remainders, bf16 storage) over blocks of 64 rows:
 // part[rb][col]; summed by db_reduce in a fixed order
+// Each thread owns 16 bytes of a row (8 bf16 or 4 float columns; cols is a multiple of that: 4H with H % 8 == 0
+// for bf16, 4H for fp32) and walks its 64 rows with that vector load.
 template <typename TE>
 __global__ __launch_bounds__(256) void lstm_bias_partial_kernel(const TE* __restrict__ dG,
                                                                const TE* __restrict__ dGlo, int rows, int cols,
                                                                float* __restrict__ part) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
+  constexpr int VEC = 16 / sizeof(TE);
+  const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
   if (col >= cols) return;
   const int r0 = blockIdx.y * 64;
   const int r1 = r0 + 64 < rows ? r0 + 64 : rows;
-  float s = 0.f;
+  float s[VEC];
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) s[i] = 0.f;
+  auto add = [&](const TE* base, int r) {
+    const uint4 q = *reinterpret_cast<const uint4*>(base + (int64_t)r * cols + col);
+    if constexpr (sizeof(TE) == 2) {
+      s[0] += lo_bf16(q.x); s[1] += hi_bf16(q.x); s[2] += lo_bf16(q.y); s[3] += hi_bf16(q.y);
+      s[4] += lo_bf16(q.z); s[5] += hi_bf16(q.z); s[6] += lo_bf16(q.w); s[7] += hi_bf16(q.w);
+    } else {
+      s[0] += __builtin_bit_cast(float, q.x); s[1] += __builtin_bit_cast(float, q.y);
+      s[2] += __builtin_bit_cast(float, q.z); s[3] += __builtin_bit_cast(float, q.w);
+    }
+  };
+#pragma unroll 4
   for (int r = r0; r < r1; ++r) {
-    s += ld_elem<TE>(dG, (int64_t)r * cols + col);
-    if (dGlo) s += ld_elem<TE>(dGlo, (int64_t)r * cols + col);
+    add(dG, r);
+    if (dGlo) add(dGlo, r);
   }
-  part[(int64_t)blockIdx.y * cols + col] = s;
+#pragma unroll
+  for (int i = 0; i < VEC; ++i) part[(int64_t)blockIdx.y * cols + col + i] = s[i];
 }
 
 namespace {
@@ -147,7 +164,7 @@ struct LsLayout {
   // bf16 storage: fragment-major operands of the fused step kernels
   size_t Wfrag;            // W_hh (forward) or its transpose (backward) of the layer being processed
   size_t hF[2][2];         // h of the previous / next step, [slot][value, remainder]
-  size_t dGF[2][2];        // gate gradients of the next / this step
+  size_t dGF[2];           // gate gradients (bf16 values) of the next / this step
   int nrb;
   std::vector<GemmPlan> p_gx, p_dwi, p_dx;
   GemmPlan p_rec, p_drec, p_dwh;
@@ -212,11 +229,10 @@ LsLayout make_ls_layout(const ls_shape* s) {
   L.dbpart = take((size_t)L.nrb * 4 * H * 4);
   L.partial = take(pb);
   L.Wfrag = bf ? take((size_t)4 * H * H * L.e) : 0;
-  for (int sl = 0; sl < 2; ++sl)
-    for (int k = 0; k < 2; ++k) {
-      L.hF[sl][k] = bf ? take((size_t)L.BH * L.e) : 0;
-      L.dGF[sl][k] = bf ? take((size_t)4 * L.BH * L.e) : 0;
-    }
+  for (int sl = 0; sl < 2; ++sl) {
+    for (int k = 0; k < 2; ++k) L.hF[sl][k] = bf ? take((size_t)L.BH * L.e) : 0;
+    L.dGF[sl] = bf ? take((size_t)4 * L.BH * L.e) : 0;
+  }
   L.total = off;
   return L;
 }
@@ -354,26 +370,24 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     if constexpr (bf) {   // one kernel per step: da_{t+1} W_hh and the cell derivative of step t
       uint16_t* WTF = reinterpret_cast<uint16_t*>(w + L.Wfrag);
       LS_TRY(launch_ls_wfrag(W_hh[l], WTF, H, true, st));
-      uint16_t* dGF[2][2];
-      for (int sl = 0; sl < 2; ++sl)
-        for (int k = 0; k < 2; ++k) dGF[sl][k] = reinterpret_cast<uint16_t*>(w + L.dGF[sl][k]);
+      uint16_t* dGF[2];
+      for (int sl = 0; sl < 2; ++sl) dGF[sl] = reinterpret_cast<uint16_t*>(w + L.dGF[sl]);
       for (int t = T - 1; t >= -1; --t) {   // t = -1: the product alone, for the gradient of the initial h
         LstmStepBwd q;
         q.WTF = WTF;
-        q.dGnF_hi = t + 1 < T ? dGF[(t + 1) & 1][0] : nullptr;
-        q.dGnF_lo = t + 1 < T ? dGF[(t + 1) & 1][1] : nullptr;
+        q.dGnF = t + 1 < T ? dGF[(t + 1) & 1] : nullptr;
         q.dhT = dhT_l;
         q.dcs = dcs;
         q.lengths = lengths; q.t = t; q.T = T; q.B = B; q.H = H;
         q.gates = nullptr; q.c_prev = q.c_new = q.dout_t = nullptr;
-        q.dG_hi = q.dG_lo = q.dGF_hi = q.dGF_lo = nullptr;
+        q.dG_hi = q.dG_lo = q.dGF = nullptr;
         q.dh0_out = dhs;
         if (t >= 0) {
           q.gates = gates + (size_t)t * B * 4 * H;
           q.c_prev = cs + (size_t)t * BH; q.c_new = cs + (size_t)(t + 1) * BH;
           q.dout_t = dout + (size_t)t * BH;
           q.dG_hi = dGE + (size_t)t * B * 4 * H; q.dG_lo = dGlo + (size_t)t * B * 4 * H;
-          q.dGF_hi = dGF[t & 1][0]; q.dGF_lo = dGF[t & 1][1];
+          q.dGF = dGF[t & 1];
         }
         LS_TRY(launch_lstm_step_bwd(q, st));
       }
@@ -413,8 +427,11 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
       g.splits = L.p_dwi[l].splits; g.partial = partial;
       LS_TRY(launch_gemm(g, bf, L.p_dwi[l].big_tile, st));
     }
-    hipLaunchKernelGGL(lstm_bias_partial_kernel<TE>, dim3((4 * H + 255) / 256, L.nrb), dim3(256), 0, st, dGE, dGlo, TB,
-                       4 * H, dbpart);
+    {
+      constexpr int per_block = 256 * (16 / (int)sizeof(TE));   // columns one block covers
+      hipLaunchKernelGGL(lstm_bias_partial_kernel<TE>, dim3((4 * H + per_block - 1) / per_block, L.nrb), dim3(256), 0,
+                         st, dGE, dGlo, TB, 4 * H, dbpart);
+    }
     LS_TRY(hipGetLastError());
     LS_TRY(launch_db_reduce(dbpart, L.nrb, 4 * H, db[l], st));
     float* dinp = l == 0 ? dx : reinterpret_cast<float*>(w + L.dio[l & 1]);
