@@ -202,3 +202,26 @@ def test_lstm_rejects_bad_arguments_before_any_launch():
     rc = bd.lstm_stack_bwd(sh, 0x100, 0x200, W, W, 0x600, None, None, 0x400, 1 << 40, 0x500, W, None, W, None, None, 0,
                            check=False)
     assert rc == 1                                       # dW_hh is required
+
+
+# ---------------------------------------------------------------- skip_pad_rows
+def test_skip_pad_rows_is_validated_and_sizes_the_workspace():
+    s0 = _shape(dtype=bd.AS_BF16)
+    s1 = _shape(dtype=bd.AS_BF16)
+    s1.skip_pad_rows = 1
+    assert bd.attn_softmax_workspace_bytes(s1) > bd.attn_softmax_workspace_bytes(s0) > 0
+    bad = _shape(dtype=bd.AS_BF16)
+    bad.skip_pad_rows = 2
+    assert bd.attn_softmax_workspace_bytes(bad) == 0
+    assert _call_fwd(bad) == 2 and "skip_pad_rows=2" in bd.attn_softmax_last_error()
+    # the row map exists only with row compaction
+    p, n, ld = ctypes.c_void_p(), ctypes.c_size_t(), ctypes.c_int64()
+    h = lib.load_library()
+    rc = h.attn_softmax_view(ctypes.byref(s0), 0xB000, bd.AS_VIEW_ROW_POS, ctypes.byref(p), ctypes.byref(n),
+                             ctypes.byref(ld))
+    assert rc == 2
+    rc = h.attn_softmax_view(ctypes.byref(s1), 0xB000, bd.AS_VIEW_ROW_POS, ctypes.byref(p), ctypes.byref(n),
+                             ctypes.byref(ld))
+    assert rc == 0 and n.value == s1.T * s1.B * 4 and ld.value == s1.B
+    # the per-step entry points ignore the flag
+    assert bd.attn_softmax_step_workspace_bytes(s1) == bd.attn_softmax_step_workspace_bytes(s0)
