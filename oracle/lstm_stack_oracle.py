@@ -21,6 +21,14 @@ h_t of layer l.  Sentences are right-padded: at steps t >= lengths[b] sentence b
 keeps its state (h_t = h_{t-1}, c_t = c_{t-1}) and the layer's output for that
 step is 0, so the final state is the state after the sentence's last word.
 
+Dropout (section 4.2 names "a dropout of 0.3" and no placement): the usual placement for
+stacked LSTMs, on the connections BETWEEN layers only, never on the recurrent ones and
+not on the top layer's output (the attentional state has its own).  `drop` is the
+array of multipliers [L-1, T, B, H] (0 where dropped, 1/(1-p) where kept) that layer
+l+1 sees on the output of layer l; the random decisions are made by the caller
+(train_extras_oracle.dropout_multiplier over (L-1)*T "steps", i.e. element (l,t,b,j) has
+flat index ((l*T + t)*B + b)*H + j) and passed in.
+
 Everything is plain numpy float64, one time step after the other, no blocking.
 """
 from __future__ import annotations
@@ -32,7 +40,7 @@ def _sigmoid(a):
     return 0.5 * (1.0 + np.tanh(0.5 * a))      # = 1 / (1 + exp(-a)), without overflow for large |a|
 
 
-def forward(x, lengths, W_ih, W_hh, b, h0=None, c0=None):
+def forward(x, lengths, W_ih, W_hh, b, h0=None, c0=None, drop=None):
     """x [T,B,I0]; lengths [B] (clamped to [0,T]); per layer l: W_ih[l] [4H,I_l] (I_0 = I0, I_l = H),
     W_hh[l] [4H,H], b[l] [4H]; h0, c0 [L,B,H] or None (zeros).
     Returns y [T,B,H] (top layer, 0 at padded steps), hT, cT [L,B,H], and `saved` for backward()."""
@@ -72,7 +80,9 @@ def forward(x, lengths, W_ih, W_hh, b, h0=None, c0=None):
         hT[l], cT[l] = h, c
         saved.append(dict(inp=inp, hs=hs, cs=cs, gates=gates, Wi=Wi, Wh=Wh))
         inp = out
-    return dict(y=inp, hT=hT, cT=cT, saved=saved, valid=valid)
+        if drop is not None and l + 1 < L:
+            inp = out * np.asarray(drop[l], dtype=np.float64)       # what the next layer reads
+    return dict(y=inp, hT=hT, cT=cT, saved=saved, valid=valid, drop=drop)
 
 
 def backward(fwd, dy, dhT=None, dcT=None):
@@ -117,4 +127,6 @@ def backward(fwd, dy, dhT=None, dcT=None):
         dW_ih[l], dW_hh[l], db[l] = dWi, dWh, dbl
         dh0[l], dc0[l] = dh, dc
         dout = dinp
+        if fwd.get("drop") is not None and l > 0:
+            dout = dinp * np.asarray(fwd["drop"][l - 1], dtype=np.float64)   # back through the mask on layer l-1's output
     return dict(dx=dout, dW_ih=dW_ih, dW_hh=dW_hh, db=db, dh0=dh0, dc0=dc0)

@@ -191,3 +191,45 @@ def test_every_gradient_matches_central_differences():
         nu = numeric(arr)
         err = np.abs(nu - an).max() / max(1.0, np.abs(an).max())
         assert err < 1e-7, (name, err)
+
+
+# ------------------------------------------------------------------ dropout between the layers
+def test_dropout_of_ones_changes_nothing_and_a_fixed_mask_matches_central_differences():
+    x, lengths, W_ih, W_hh, b, h0, c0, rng = _case(seed=21, T=4, B=3, I0=2, H=3, L=3, lengths=[4, 2, 3])
+    R = rng.standard_normal((4, 3, 3))
+    Rh, Rc = rng.standard_normal(h0.shape), rng.standard_normal(c0.shape)
+    plain = lo.forward(x, lengths, W_ih, W_hh, b, h0, c0)
+    ones = lo.forward(x, lengths, W_ih, W_hh, b, h0, c0, drop=np.ones((2, 4, 3, 3)))
+    assert np.array_equal(plain["y"], ones["y"]) and np.array_equal(plain["cT"], ones["cT"])
+    drop = (rng.random((2, 4, 3, 3)) < 0.6) / 0.6            # a fixed mask with keep rate 0.6
+    f = lo.forward(x, lengths, W_ih, W_hh, b, h0, c0, drop=drop)
+    assert not np.allclose(f["y"], plain["y"])
+    g = lo.backward(f, R, Rh, Rc)
+    eps = 1e-6
+    for name, arr, an in [("dx", x, g["dx"]), ("dW_hh0", W_hh[0], g["dW_hh"][0]), ("dW_ih1", W_ih[1], g["dW_ih"][1]),
+                          ("db2", b[2], g["db"][2]), ("dh0", h0, g["dh0"])]:
+        nu = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            k = it.multi_index
+            old = arr[k]
+            arr[k] = old + eps
+            up = _scalar(lo.forward(x, lengths, W_ih, W_hh, b, h0, c0, drop=drop), R, Rh, Rc)
+            arr[k] = old - eps
+            dn = _scalar(lo.forward(x, lengths, W_ih, W_hh, b, h0, c0, drop=drop), R, Rh, Rc)
+            arr[k] = old
+            nu[k] = (up - dn) / (2 * eps)
+        err = np.abs(nu - an).max() / max(1.0, np.abs(an).max())
+        assert err < 1e-7, (name, err)
+
+
+def test_a_fully_dropped_layer_output_cuts_the_stack():
+    """All of layer 0's outputs dropped: the layers above see zeros, and nothing below receives gradient
+    from the top layer's outputs."""
+    x, lengths, W_ih, W_hh, b, h0, c0, rng = _case(seed=22, T=5, B=2, I0=3, H=4, L=2, lengths=[5, 3])
+    drop = np.zeros((1, 5, 2, 4))
+    f = lo.forward(x, lengths, W_ih, W_hh, b, h0, c0, drop=drop)
+    alone = lo.forward(np.zeros((5, 2, 4)), lengths, W_ih[1:], W_hh[1:], b[1:], h0[1:], c0[1:])
+    assert np.allclose(f["y"], alone["y"], atol=1e-15)
+    g = lo.backward(f, rng.standard_normal((5, 2, 4)))
+    assert np.all(g["dx"] == 0) and np.all(g["dW_ih"][0] == 0) and np.all(g["dW_hh"][0] == 0)
