@@ -44,6 +44,16 @@ typedef struct {
   int32_t H;       /* hidden state size: >= 1 */
   int32_t L;       /* layers: 1..16 */
   int32_t dtype;   /* as_dtype */
+  /* Dropout on the connections BETWEEN layers (section 4.2 names "a dropout of 0.3" and no
+   * placement; the recurrent connections and the top layer's output y are left alone):
+   * what layer l+1 reads of layer l's output element (t,b,j), flat index
+   * i = ((l*T + t)*B + b)*H + j, is kept iff word (i & 3) of philox4x32-10(counter = i >> 2,
+   * key = dropout_seed) is >= floor(dropout_p * 2^32), kept elements are multiplied by
+   * 1/(1 - dropout_p); the backward pass draws the same words again.  0 <= dropout_p < 1,
+   * 0 switches it off; the caller changes the seed from step to step (and uses different
+   * seeds for the encoder and the decoder). */
+  float dropout_p;
+  uint64_t dropout_seed;
 } ls_shape;
 
 /* Bytes of workspace fwd+bwd need; 0 if the shape is invalid. */

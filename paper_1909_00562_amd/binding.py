@@ -45,7 +45,8 @@ class AsShape(ctypes.Structure):
 
 class LsShape(ctypes.Structure):
     _fields_ = [("T", ctypes.c_int32), ("B", ctypes.c_int32), ("I", ctypes.c_int32), ("H", ctypes.c_int32),
-                ("L", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("L", ctypes.c_int32), ("dtype", ctypes.c_int32), ("dropout_p", ctypes.c_float),
+                ("dropout_seed", ctypes.c_uint64)]
 
 
 class AsAdam(ctypes.Structure):
@@ -323,7 +324,8 @@ class DeviceLstm:
     x [T,B,I], lengths [B], W_ih / W_hh / b: lists of L arrays, h0 / c0 [L,B,H] or None (numpy, values already
     representable in the storage type)."""
 
-    def __init__(self, x, lengths, W_ih, W_hh, b, h0=None, c0=None, dtype="f32", device="cuda:0"):
+    def __init__(self, x, lengths, W_ih, W_hh, b, h0=None, c0=None, dtype="f32", device="cuda:0", dropout_p=0.0,
+                 dropout_seed=0):
         import torch
         self.torch = torch
         self.dev = torch.device(device)
@@ -333,7 +335,7 @@ class DeviceLstm:
         T, B, I = x.shape
         L, H = len(W_ih), W_hh[0].shape[1]
         self.T, self.B, self.I, self.H, self.L = T, B, I, H, L
-        self.shape = LsShape(T, B, I, H, L, AS_BF16 if bf else AS_F32)
+        self.shape = LsShape(T, B, I, H, L, AS_BF16 if bf else AS_F32, float(dropout_p), int(dropout_seed))
         f32 = torch.float32
 
         def up(a, dt=tdt):

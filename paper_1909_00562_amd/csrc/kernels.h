@@ -77,6 +77,10 @@ struct LstmStepFwd {
   uint16_t *hFn_hi, *hFn_lo, *hE_new, *out, *out_lo;
   const int32_t* lengths;
   int t, T, B, H;
+  // dropout on out / out_lo (drop_thr = 0: none): element (b, j) of this step has flat index drop_index0 + b*H + j
+  uint32_t drop_thr;
+  float drop_scale;
+  uint64_t drop_seed, drop_index0;
 };
 hipError_t launch_lstm_step_fwd(const LstmStepFwd& p, hipStream_t st);
 // Backward of step t: WTF = W_hh^T [H,4H] fragment-major (launch_ls_wfrag, backward); dGnF: gate gradients
@@ -94,6 +98,10 @@ struct LstmStepBwd {
   float* dh0_out;
   const int32_t* lengths;
   int t, T, B, H;
+  // the dropout the forward step applied to this layer's output: dout_t goes back through the same mask
+  uint32_t drop_thr;
+  float drop_scale;
+  uint64_t drop_seed, drop_index0;
 };
 hipError_t launch_lstm_step_bwd(const LstmStepBwd& p, hipStream_t st);
 // W_hh [4H,H] of one layer into the fragment-major form the forward (backward = false) or backward step reads

@@ -52,7 +52,9 @@ __global__ __launch_bounds__(256) void lstm_cell_fwd_kernel(float* __restrict__ 
                                                            float* __restrict__ c_new, float* __restrict__ hf,
                                                            const float* __restrict__ h_prev, float* __restrict__ h_new,
                                                            float* __restrict__ out, const int32_t* __restrict__ lengths,
-                                                           int t, int T, int B, int H) {
+                                                           int t, int T, int B, int H, uint32_t drop_thr,
+                                                           float drop_scale, uint64_t drop_seed,
+                                                           uint64_t drop_index0) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= B * H) return;
   const int b = idx / H, j = idx - b * H;
@@ -68,7 +70,8 @@ __global__ __launch_bounds__(256) void lstm_cell_fwd_kernel(float* __restrict__ 
     c_new[idx] = cn;
     hf[idx] = hn;
     h_new[idx] = hn;
-    out[idx] = hn;
+    // dropout on what the next layer reads (drop_thr = 0: none)
+    out[idx] = drop_thr ? hn * dropout_mult(drop_index0 + (uint64_t)idx, drop_seed, drop_thr, drop_scale) : hn;
   } else {
     c_new[idx] = cp;
     h_new[idx] = h_prev[idx];
@@ -85,7 +88,8 @@ __global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const float* __restr
                                                            const float* __restrict__ dout_t, float* __restrict__ dhs,
                                                            float* __restrict__ dcs, float* __restrict__ dG_t,
                                                            const int32_t* __restrict__ lengths, int t, int T, int B,
-                                                           int H) {
+                                                           int H, uint32_t drop_thr, float drop_scale,
+                                                           uint64_t drop_seed, uint64_t drop_index0) {
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= B * H) return;
   const int b = idx / H, j = idx - b * H;
@@ -95,7 +99,9 @@ __global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const float* __restr
   if (t < len) {
     const float* g4 = gates + (int64_t)b * 4 * H + j;
     const float i = g4[0], f = g4[H], g = g4[2 * H], o = g4[3 * H];
-    const float dh = dout_t[idx] + dhs[idx];
+    float dy = dout_t[idx];   // back through the mask the forward pass put on this layer's output
+    if (drop_thr) dy *= dropout_mult(drop_index0 + (uint64_t)idx, drop_seed, drop_thr, drop_scale);
+    const float dh = dy + dhs[idx];
     const float tc = tanhf(c_new[idx]);
     const float dc = dcs[idx] + dh * o * (1.f - tc * tc);
     d4[0] = dc * g * i * (1.f - i);
@@ -174,6 +180,7 @@ bool ls_shape_ok(const ls_shape* s) {
   if (!s) return false;
   if (s->T < 1 || s->B < 1 || s->I < 1 || s->H < 1 || s->L < 1 || s->L > 16) return false;
   if (s->dtype != AS_F32 && s->dtype != AS_BF16) return false;
+  if (!(s->dropout_p >= 0.f && s->dropout_p < 1.f)) return false;
   if (s->dtype == AS_BF16 && ((s->I % 8) != 0 || (s->H % 8) != 0)) return false;
   if ((int64_t)s->T * s->B > (1 << 24) || s->H > (1 << 16) || s->I > (1 << 16)) return false;
   if ((int64_t)s->T * s->B * 4 * s->H > ((int64_t)1 << 34)) return false;
@@ -254,7 +261,8 @@ as_status check_ls(const ls_shape* s, void* ws, size_t ws_bytes, LsLayout* L) {
   if (s->dtype == AS_BF16 && s->T >= 1 && s->B >= 1 && s->I >= 1 && s->H >= 1 && ((s->I % 8) != 0 || (s->H % 8) != 0))
     return set_error(AS_ERR_ALIGN, "AS_BF16 needs I %% 8 == 0 and H %% 8 == 0 (I=%d H=%d)", s->I, s->H);
   if (!ls_shape_ok(s))
-    return set_error(AS_ERR_SHAPE, "bad shape T=%d B=%d I=%d H=%d L=%d", s->T, s->B, s->I, s->H, s->L);
+    return set_error(AS_ERR_SHAPE, "bad shape T=%d B=%d I=%d H=%d L=%d dropout_p=%g", s->T, s->B, s->I, s->H, s->L,
+                     (double)s->dropout_p);
   if (!ws) return set_error(AS_ERR_NULL, "workspace is NULL");
   if (!al16(ws)) return set_error(AS_ERR_ALIGN, "workspace %p is not 16-byte aligned", ws);
   *L = make_ls_layout(s);
@@ -286,6 +294,9 @@ as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     TE* hE = reinterpret_cast<TE*>(w + L.hE[l]);
     TE* out = reinterpret_cast<TE*>(l + 1 < NL ? w + L.out[l] : y);
     TE* out_lo = (bf && l + 1 < NL) ? reinterpret_cast<TE*>(w + L.out_lo[l]) : nullptr;
+    // dropout sits between the layers: on what layer l+1 reads, never on the top layer's output
+    const uint32_t drop_thr = (l + 1 < NL && s->dropout_p > 0.f) ? (uint32_t)((double)s->dropout_p * 4294967296.0) : 0u;
+    const float drop_scale = 1.f / (1.f - s->dropout_p);
     TE* hF[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}};
     if (bf)
       for (int sl = 0; sl < 2; ++sl)
@@ -315,6 +326,8 @@ as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
         f.hE_new = hE + (size_t)(t + 1) * BH;
         f.out = out + (size_t)t * BH; f.out_lo = out_lo ? out_lo + (size_t)t * BH : nullptr;
         f.lengths = lengths; f.t = t; f.T = T; f.B = B; f.H = H;
+        f.drop_thr = drop_thr; f.drop_scale = drop_scale; f.drop_seed = s->dropout_seed;
+        f.drop_index0 = ((uint64_t)l * T + t) * (uint64_t)BH;
         LS_TRY(launch_lstm_step_fwd(f, st));
       }
     } else {              // fp32: the recurrent product and the cell as two launches per step
@@ -330,7 +343,8 @@ as_status ls_fwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
         LS_TRY(launch_gemm(g, false, L.p_rec.big_tile, st));
         hipLaunchKernelGGL(lstm_cell_fwd_kernel, dim3(nb), dim3(256), 0, st, Gt, cs + (size_t)t * BH,
                            cs + (size_t)(t + 1) * BH, hf, hE + (size_t)t * BH, hE + (size_t)(t + 1) * BH,
-                           out + (size_t)t * BH, lengths, t, T, B, H);
+                           out + (size_t)t * BH, lengths, t, T, B, H, drop_thr, drop_scale, s->dropout_seed,
+                           ((uint64_t)l * T + t) * (uint64_t)BH);
         LS_TRY(hipGetLastError());
       }
     }
@@ -365,6 +379,8 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     const TE* hE = reinterpret_cast<const TE*>(w + L.hE[l]);
     const char* xin = l == 0 ? x : w + L.out[l - 1];
     const float* dhT_l = dhT ? dhT + (size_t)l * BH : nullptr;
+    const uint32_t drop_thr = (l + 1 < NL && s->dropout_p > 0.f) ? (uint32_t)((double)s->dropout_p * 4294967296.0) : 0u;
+    const float drop_scale = 1.f / (1.f - s->dropout_p);
     hipLaunchKernelGGL(lstm_copy_or_zero_kernel, dim3(nb), dim3(256), 0, st, dcT ? dcT + (size_t)l * BH : nullptr, dcs, BH);
     LS_TRY(hipGetLastError());
     if constexpr (bf) {   // one kernel per step: da_{t+1} W_hh and the cell derivative of step t
@@ -379,6 +395,8 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
         q.dhT = dhT_l;
         q.dcs = dcs;
         q.lengths = lengths; q.t = t; q.T = T; q.B = B; q.H = H;
+        q.drop_thr = drop_thr; q.drop_scale = drop_scale; q.drop_seed = s->dropout_seed;
+        q.drop_index0 = ((uint64_t)l * T + (t < 0 ? 0 : t)) * (uint64_t)BH;
         q.gates = nullptr; q.c_prev = q.c_new = q.dout_t = nullptr;
         q.dG_hi = q.dG_lo = q.dGF = nullptr;
         q.dh0_out = dhs;
@@ -398,7 +416,7 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
         float* dGt = dGE + (size_t)t * B * 4 * H;
         hipLaunchKernelGGL(lstm_cell_bwd_kernel, dim3(nb), dim3(256), 0, st, gates + (size_t)t * B * 4 * H,
                            cs + (size_t)t * BH, cs + (size_t)(t + 1) * BH, dout + (size_t)t * BH, dhs, dcs, dGt, lengths,
-                           t, T, B, H);
+                           t, T, B, H, drop_thr, drop_scale, s->dropout_seed, ((uint64_t)l * T + t) * (uint64_t)BH);
         LS_TRY(hipGetLastError());
         GemmArgs g;       // dh_{t-1} (+)= da_t W_hh: valid rows were cleared, padded rows have da_t = 0 and keep theirs
         g.seg(dGt, 4 * H, 0, W_hh[l], H, 0, 4 * H);

@@ -188,6 +188,14 @@ __global__ __launch_bounds__(64 * LSF_KS) void lstm_step_fwd_kernel(LstmStepFwd 
     *reinterpret_cast<ls_u32x2_t*>(p.hE_new + idx) = hi;
     *reinterpret_cast<ls_u32x2_t*>(p.hFn_hi + fidx) = hi;
     *reinterpret_cast<ls_u32x2_t*>(p.hFn_lo + fidx) = lo;
+    if (p.drop_thr) {   // what the next layer reads: the lane's four units are one block of the generator
+      uint32_t w[4];
+      dropout_words4((p.drop_index0 + (uint64_t)idx) >> 2, p.drop_seed, w);
+      float o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = w[e] >= p.drop_thr ? hn[e] * p.drop_scale : 0.f;
+      ls_split4(o, hi, lo);
+    }
     *reinterpret_cast<ls_u32x2_t*>(p.out + idx) = hi;
     if (p.out_lo) *reinterpret_cast<ls_u32x2_t*>(p.out_lo + idx) = lo;
   } else {   // padded step: the state passes through, the layer's output is 0
@@ -236,6 +244,12 @@ __global__ __launch_bounds__(64 * LSB_KS) void lstm_step_bwd_kernel(LstmStepBwd 
     cn = *reinterpret_cast<const f32x4_t*>(p.c_new + idx);
     dy = *reinterpret_cast<const f32x4_t*>(p.dout_t + idx);
     dcs = *reinterpret_cast<const f32x4_t*>(p.dcs + idx);
+    if (p.drop_thr) {   // back through the mask the forward step put on this layer's output
+      uint32_t w[4];
+      dropout_words4((p.drop_index0 + (uint64_t)idx) >> 2, p.drop_seed, w);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dy[e] = w[e] >= p.drop_thr ? dy[e] * p.drop_scale : 0.f;
+    }
   }
 
   f32x16_t acc;

@@ -172,6 +172,10 @@ def test_lstm_workspace_bytes():
                 dict(dtype=bd.AS_BF16, H=12), dict(dtype=bd.AS_BF16, I=12)):
         assert bd.lstm_stack_workspace_bytes(_ls(**bad)) == 0, bad
     assert bd.lstm_stack_workspace_bytes(_ls(L=4)) > bd.lstm_stack_workspace_bytes(_ls(L=2))
+    for p_drop, ok in ((0.3, True), (0.0, True), (1.0, False), (-0.1, False)):
+        sh = _ls()
+        sh.dropout_p = p_drop
+        assert (bd.lstm_stack_workspace_bytes(sh) > 0) == ok, p_drop
 
 
 def test_lstm_rejects_bad_arguments_before_any_launch():

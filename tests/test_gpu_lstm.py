@@ -18,7 +18,8 @@ def run_gpu(inp, use_states=True, **kw):
     import torch
     import paper_1909_00562_amd as lib
     d = lib.DeviceLstm(inp.x, inp.lengths, inp.W_ih, inp.W_hh, inp.b, inp.h0 if use_states else None,
-                       inp.c0 if use_states else None, dtype=inp.dtype, **kw)
+                       inp.c0 if use_states else None, dtype=inp.dtype, dropout_p=getattr(inp, "dropout_p", 0.0),
+                       dropout_seed=getattr(inp, "dropout_seed", 0), **kw)
     d.fwd()
     d.sync()
     f = dict(y=_host(d.y), hT=_host(d.hT), cT=_host(d.cT))
@@ -33,9 +34,19 @@ def run_gpu(inp, use_states=True, **kw):
     return f, g, d
 
 
+def oracle_drop(inp):
+    """Multipliers on the connections between the layers, [L-1, T, B, H] (None when dropout is off)."""
+    p = getattr(inp, "dropout_p", 0.0)
+    if p <= 0.0 or inp.L < 2:
+        return None
+    from oracle import train_extras_oracle as tx
+    return tx.dropout_multiplier((inp.L - 1) * inp.T, inp.B, inp.H, p, inp.dropout_seed).reshape(
+        inp.L - 1, inp.T, inp.B, inp.H)
+
+
 def run_oracle(inp, use_states=True):
     fo = lo.forward(inp.x, inp.lengths, inp.W_ih, inp.W_hh, inp.b, inp.h0 if use_states else None,
-                    inp.c0 if use_states else None)
+                    inp.c0 if use_states else None, drop=oracle_drop(inp))
     go = lo.backward(fo, inp.dy, inp.dhT if use_states else None, inp.dcT if use_states else None)
     return fo, go
 
@@ -201,3 +212,32 @@ def test_encoder_decoder_attention_chain_fp32():
         pu.assert_close(_host(dec.dW_hh[l]), dgo["dW_hh"][l], "f32", f"decoder dW_hh[{l}]")
         pu.assert_close(_host(enc.dW_ih[l]), ego["dW_ih"][l], "f32", f"encoder dW_ih[{l}]")
         pu.assert_close(_host(enc.db[l]), ego["db"][l], "f32", f"encoder db[{l}]")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(6, 4, 24, 16, 3), (9, 5, 72, 40, 2), (20, 32, 64, 128, 4)])
+def test_lstm_dropout_between_layers(shape, dtype):
+    """Same words of the generator on both sides (the decision is integer work): with them every tensor
+    agrees to the usual tolerance, and the run differs from the one without dropout."""
+    T, B, I, H, L = shape
+    inp = make_lstm_inputs(T, B, I, H, L, seed=900 + T + H, dtype=dtype)
+    inp.dropout_p, inp.dropout_seed = 0.3, 20190900562 + T
+    f, g, _ = run_gpu(inp)
+    fo, go = run_oracle(inp)
+    compare(inp, f, g, fo, go)
+    plain = make_lstm_inputs(T, B, I, H, L, seed=900 + T + H, dtype=dtype)
+    fp, _, _ = run_gpu(plain)
+    assert not np.array_equal(fp["y"], f["y"])
+    # rate 0 with a seed set is the same as no dropout, bit for bit
+    zero = make_lstm_inputs(T, B, I, H, L, seed=900 + T + H, dtype=dtype)
+    zero.dropout_p, zero.dropout_seed = 0.0, 77
+    fz, gz, _ = run_gpu(zero)
+    assert np.array_equal(fz["y"], fp["y"])
+
+
+def test_lstm_dropout_paper_size_sixteen_sentences():
+    inp = make_lstm_inputs(50, 16, 512, 1024, 4, seed=1910, dtype="bf16", min_len=20)
+    inp.dropout_p, inp.dropout_seed = 0.3, 5
+    f, g, _ = run_gpu(inp)
+    fo, go = run_oracle(inp)
+    compare(inp, f, g, fo, go)
