@@ -188,6 +188,9 @@ typedef enum {
 } as_stage;
 
 as_status attn_softmax_profile_enable(int enable);
+/* Restrict the timing to the stages whose bit (1 << as_stage) is set, e.g. to keep the events of a
+ * measurement out of the small kernels' way; attn_softmax_profile_enable selects all stages again. */
+as_status attn_softmax_profile_select(uint64_t stage_mask);
 /* ms_total[AS_STAGE_COUNT], launches[AS_STAGE_COUNT]; either may be NULL. */
 as_status attn_softmax_profile_read(double* ms_total, int64_t* launches);
 

@@ -25,6 +25,7 @@ STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "g
                "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam", "compact"]
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
+           "attn_softmax_profile_select",
            "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
            "attn_softmax_step_fwd", "lstm_stack_workspace_bytes", "lstm_stack_fwd", "lstm_stack_bwd"]
 
@@ -81,6 +82,8 @@ def load_library():
     lib.attn_softmax_last_error.argtypes = []
     lib.attn_softmax_profile_enable.restype = ctypes.c_int
     lib.attn_softmax_profile_enable.argtypes = [ctypes.c_int]
+    lib.attn_softmax_profile_select.restype = ctypes.c_int
+    lib.attn_softmax_profile_select.argtypes = [ctypes.c_uint64]
     lib.attn_softmax_profile_read.restype = ctypes.c_int
     lib.attn_softmax_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.attn_softmax_step_workspace_bytes.restype = sz
@@ -226,6 +229,14 @@ def lstm_stack_bwd(shape, x, lengths, W_ih, W_hh, dy, dhT, dcT, workspace, works
 
 def attn_softmax_profile_enable(enable: bool):
     _check(load_library().attn_softmax_profile_enable(1 if enable else 0))
+
+
+def attn_softmax_profile_select(stages) -> None:
+    """Time only the named stages (names as in STAGE_NAMES) until profiling is enabled again."""
+    mask = 0
+    for name in stages:
+        mask |= 1 << STAGE_NAMES.index(name)
+    _check(load_library().attn_softmax_profile_select(mask))
 
 
 def attn_softmax_profile_read() -> Dict[str, dict]:

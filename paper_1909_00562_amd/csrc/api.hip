@@ -46,6 +46,7 @@ using namespace asx;
 // ---- profiling: HIP events around every launch ---------------------------------
 struct Prof {
   bool on = false;
+  uint64_t mask = ~0ull;   // stages that are timed while on (bit = as_stage)
   struct Rec {
     int stage;
     hipEvent_t a, b;
@@ -72,7 +73,7 @@ struct StageTimer {
   Prof::Rec rec{0, nullptr, nullptr};
   bool live = false;
   StageTimer(int stage, hipStream_t s) : st(s) {
-    if (!g_prof.on) return;
+    if (!g_prof.on || !((g_prof.mask >> stage) & 1ull)) return;
     rec.stage = stage;
     rec.a = g_prof.get();
     rec.b = g_prof.get();
@@ -638,6 +639,12 @@ as_status attn_softmax_profile_enable(int enable) {
     g_prof.launches[i] = 0;
   }
   g_prof.on = enable != 0;
+  g_prof.mask = ~0ull;
+  return AS_OK;
+}
+
+as_status attn_softmax_profile_select(uint64_t stage_mask) {
+  g_prof.mask = stage_mask;
   return AS_OK;
 }
 
