@@ -122,17 +122,18 @@ __global__ __launch_bounds__(256) void lstm_copy_or_zero_kernel(const float* __r
   if (i < n) dst[i] = src ? src[i] : 0.f;
 }
 
-// column sums of da [rows, cols] (+ its rounding remainders, bf16 storage) over blocks of 64 rows:
-// part[rb][col]; summed by db_reduce in a fixed order
-// Each thread owns 16 bytes of a row (8 bf16 or 4 float columns; cols is a multiple of that: 4H with H % 8 == 0
-// for bf16, 4H for fp32) and walks its 64 rows with that vector load.
+// Column sums of da [rows, cols] (+ its rounding remainders, bf16 storage) over blocks of 64 rows:
+// part[rb][col], summed by db_reduce in a fixed order.  A thread owns 16 bytes of a row (8 bf16 or 4 float
+// columns; cols is a multiple of that: 4H with H % 8 == 0 for bf16, 4H for fp32); the block's 256 threads are
+// 64 column groups x 4 row phases (rows r0 + phase, + 4, ...), whose sums meet in LDS in a fixed order.
 template <typename TE>
 __global__ __launch_bounds__(256) void lstm_bias_partial_kernel(const TE* __restrict__ dG,
                                                                const TE* __restrict__ dGlo, int rows, int cols,
                                                                float* __restrict__ part) {
   constexpr int VEC = 16 / sizeof(TE);
-  const int col = (blockIdx.x * 256 + threadIdx.x) * VEC;
-  if (col >= cols) return;
+  __shared__ float red[4][64][VEC];
+  const int cg = threadIdx.x & 63, phase = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + cg) * VEC;
   const int r0 = blockIdx.y * 64;
   const int r1 = r0 + 64 < rows ? r0 + 64 : rows;
   float s[VEC];
@@ -148,13 +149,21 @@ __global__ __launch_bounds__(256) void lstm_bias_partial_kernel(const TE* __rest
       s[2] += __builtin_bit_cast(float, q.z); s[3] += __builtin_bit_cast(float, q.w);
     }
   };
+  if (col < cols) {
 #pragma unroll 4
-  for (int r = r0; r < r1; ++r) {
-    add(dG, r);
-    if (dGlo) add(dGlo, r);
+    for (int r = r0 + phase; r < r1; r += 4) {
+      add(dG, r);
+      if (dGlo) add(dGlo, r);
+    }
   }
 #pragma unroll
-  for (int i = 0; i < VEC; ++i) part[(int64_t)blockIdx.y * cols + col + i] = s[i];
+  for (int i = 0; i < VEC; ++i) red[phase][cg][i] = s[i];
+  __syncthreads();
+  if (phase == 0 && col < cols) {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+      part[(int64_t)blockIdx.y * cols + col + i] = ((red[0][cg][i] + red[1][cg][i]) + red[2][cg][i]) + red[3][cg][i];
+  }
 }
 
 namespace {
@@ -446,7 +455,7 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
       LS_TRY(launch_gemm(g, bf, L.p_dwi[l].big_tile, st));
     }
     {
-      constexpr int per_block = 256 * (16 / (int)sizeof(TE));   // columns one block covers
+      constexpr int per_block = 64 * (16 / (int)sizeof(TE));    // columns one block covers
       hipLaunchKernelGGL(lstm_bias_partial_kernel<TE>, dim3((4 * H + per_block - 1) / per_block, L.nrb), dim3(256), 0,
                          st, dGE, dGlo, TB, 4 * H, dbpart);
     }

@@ -230,13 +230,19 @@ __global__ __launch_bounds__(256) void xent_dlogits_kernel(TE* __restrict__ logi
     if (c0 + i < V) db_partial[(int64_t)blockIdx.y * V + c0 + i] = cs[i];
 }
 
+// 64 columns x 4 phases per block: phase p adds the row blocks p, p+4, ... of its column, the four sums meet
+// in LDS; the order of the additions is fixed
 __global__ __launch_bounds__(256) void db_reduce_kernel(const float* __restrict__ db_partial, int nrb, int V,
                                                        float* __restrict__ db_out) {
-  const int v = blockIdx.x * 256 + threadIdx.x;
-  if (v >= V) return;
+  __shared__ float red[4][64];
+  const int c = threadIdx.x & 63, phase = threadIdx.x >> 6;
+  const int v = blockIdx.x * 64 + c;
   float s = 0.f;
-  for (int r = 0; r < nrb; ++r) s += db_partial[(int64_t)r * V + v];
-  db_out[v] = s;
+  if (v < V)
+    for (int r = phase; r < nrb; r += 4) s += db_partial[(int64_t)r * V + v];
+  red[phase][c] = s;
+  __syncthreads();
+  if (phase == 0 && v < V) db_out[v] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
 }
 
 // ---- launchers ----------------------------------------------------------------
@@ -288,7 +294,7 @@ hipError_t launch_xent_dlogits(void* logits, int64_t ldV, bool e_bf16, int N, in
 }
 
 hipError_t launch_db_reduce(const float* db_partial, int nrb, int V, float* db_out, hipStream_t st) {
-  hipLaunchKernelGGL(db_reduce_kernel, dim3((V + 255) / 256), dim3(256), 0, st, db_partial, nrb, V, db_out);
+  hipLaunchKernelGGL(db_reduce_kernel, dim3((V + 63) / 64), dim3(256), 0, st, db_partial, nrb, V, db_out);
   return hipGetLastError();
 }
 
