@@ -196,6 +196,60 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x
     for (int c = 0; c < 4; ++c)
       if (col_in) bias4[c] = bf16_bits_to_f32(p.bias[col0 + vcol + c]);
   }
+  const bool plain = !DROP && !p.act_tanh && !p.gate && !p.C_lo && !p.C_dact && !(fuse && p.accumulate);
+  if (plain) {
+    // Bias only (no tanh, gate, remainder / derivative outputs, accumulation, dropout), decided once per tile:
+    // the general form below tests each of those per row group, and its branches and the arithmetic behind
+    // them were most of the write-out time of the vocabulary projection (two waves share a SIMD's vector ALU).
+    // The CH/4 reads of a round are in flight together, and the LDS writes of round ic+1 are issued when
+    // the last read of round ic has returned, so their latency hides behind that row group's stores.
+    constexpr int NR = TM * (32 / CH);
+    auto write_round = [&](int ic) {
+      const int i = ic / (32 / CH), part = ic % (32 / CH);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int trow = (r >> 2) * 8;
+          if (trow / CH != part) continue;
+          stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
+        }
+    };
+    write_round(0);
+#pragma unroll
+    for (int ic = 0; ic < NR; ++ic) {
+      const int i = ic / (32 / CH), part = ic % (32 / CH);
+      __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
+      f32x4_t v4s[CH / 4];
+#pragma unroll
+      for (int it = 0; it < CH / 4; ++it)
+        v4s[it] = *reinterpret_cast<const f32x4_t*>(stage_f + (it * 4 + vrow) * EP_LD + vcol);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int it = 0; it < CH / 4; ++it) {
+        const int nrow = i * 32 + part * CH + it * 4;            // tile row of the lane's row group (compile time)
+        const bool in = nrow < rows_left && col_in;
+        if (it == CH / 4 - 1) {
+          __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
+          if (ic + 1 < NR) write_round(ic + 1);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const f32x4_t v4 = v4s[it];
+        const uint32_t row_el = (uint32_t)nrow * ld32;           // wave-uniform: goes into the scalar offset operand
+        const float v[4] = {v4[0] + bias4[0], v4[1] + bias4[1], v4[2] + bias4[2], v4[3] + bias4[3]};
+        if constexpr (OUT_BF16) {
+          const u32x2_t hv = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          __builtin_amdgcn_raw_buffer_store_b64(hv, rs_c, in ? lane_off * 2u : kOob, row_el * 2u, 0);
+        } else {
+          const u32x4_t sv = {__builtin_bit_cast(uint32_t, v[0]), __builtin_bit_cast(uint32_t, v[1]),
+                              __builtin_bit_cast(uint32_t, v[2]), __builtin_bit_cast(uint32_t, v[3])};
+          __builtin_amdgcn_raw_buffer_store_b128(sv, rs_c, in ? lane_off * 4u : kOob, row_el * 4u, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int ic = 0; ic < TM * (32 / CH); ++ic) {
     const int i = ic / (32 / CH), part = ic % (32 / CH);
