@@ -222,7 +222,19 @@ LsLayout make_ls_layout(const ls_shape* s) {
     // bf16: the output of the layer below and the gate gradients are (value, remainder) pairs: two segments
     L.p_gx.push_back(gemm_plan(TB, 4 * H, (bf && l > 0) ? 2 * Il : Il, 1, bf, false));
     L.p_dwi.push_back(gemm_plan(4 * H, Il, TB, 1, bf, true));
-    L.p_dx.push_back(gemm_plan(TB, Il, bf ? 8 * H : 4 * H, 1, bf, false));
+    {
+      // The reduction split of this product is a function of the layer's widths alone: with a split chosen
+      // from the row count, a sentence's gradients would depend (in the last fp32 bit, then through bf16
+      // roundings below) on how many sentences share its batch.
+      GemmPlan px = gemm_plan(TB, Il, 4 * H, 1, bf, false);
+      if (bf) {
+        const int ktiles = (4 * H + 63) / 64, want = Il >= 1024 ? 2 : 4;
+        px.splits = ktiles / 8 < 1 ? 1 : (ktiles / 8 < want ? ktiles / 8 : want);
+        px.big_tile = 1;
+      }
+      L.p_dx.push_back(px);
+      mx(gemm_partial_bytes(TB, Il, 1, px.splits));
+    }
     mx(gemm_partial_bytes(4 * H, Il, 1, L.p_dwi.back().splits));
   }
   L.p_rec = gemm_plan(B, 4 * H, H, 1, false, true);      // the per-step products as launches of their own: fp32 only
@@ -464,11 +476,11 @@ as_status ls_bwd(const ls_shape* s, const LsLayout& L, const char* x, const int3
     float* dinp = l == 0 ? dx : reinterpret_cast<float*>(w + L.dio[l & 1]);
     {  // gradient of the layer's input, all steps: da W_ih
       GemmArgs g;
-      g.seg(dGE, 4 * H, 0, W_ih[l], Il, 0, 4 * H);
-      if (dGlo) g.seg(dGlo, 4 * H, 0, W_ih[l], Il, 0, 4 * H);
+      g.seg(dGE, 4 * H, 0, W_ih[l], Il, 0, 4 * H);   // (bf16: the gate gradients as rounded, like the recurrent product)
       g.a_kc = true; g.b_kc = false;
       g.M = TB; g.N = Il;
       g.C = dinp; g.ldc = Il; g.c_bf16 = false;
+      g.splits = L.p_dx[l].splits; g.partial = partial;
       LS_TRY(launch_gemm(g, bf, L.p_dx[l].big_tile, st));
     }
     if (dh0) LS_TRY(hipMemcpyAsync(dh0 + (size_t)l * BH, dhs, (size_t)BH * 4, hipMemcpyDeviceToDevice, st));
