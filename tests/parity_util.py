@@ -6,7 +6,9 @@ Tolerance rule (both storage types):
     ||x - o||_2 <= rtol * ||o||_2                     for every tensor,
 with (atol, rtol) = (0, 1e-4) on the fp32 path and (1e-3, 2e-2) on the
 bf16-input path (the figures the benchmark definition states), and rowscale =
-root-mean-square of the oracle over the last axis.  "Relative" is taken
+FLOOR x root-mean-square of the oracle over the last axis (FLOOR = 0.2 fp32,
+1 bf16).  The share of elements that need the floor at all is bounded per
+tensor (STRICT_FRAC_MAX).  "Relative" is taken
 relative to the magnitude of the row an element belongs to, because every
 output element is a sum of many products: its rounding error scales with the
 size of the terms of the sum, which the row's magnitude tracks, while |o|
@@ -15,11 +17,40 @@ are compared bit for bit.
 """
 from __future__ import annotations
 
+import os
+
 import numpy as np
 
 from oracle import attn_softmax_oracle as orc
 
 TOL = {"f32": (0.0, 1e-4), "bf16": (1e-3, 2e-2)}
+# Fraction of the row's RMS that serves as the floor of |o| in the elementwise rule.  fp32: the worst element
+# measured needs 0.14 (d_h_enc of the small configuration: scores of size ~30 stored in fp32, amplified by the
+# softmax); bf16: 0.75 (weight gradients of the LSTM at the paper's size).
+FLOOR = {"f32": 0.2, "bf16": 1.0}
+# Largest admitted share of a tensor's elements outside the plain form |x - o| <= atol + rtol * |o| (no floor):
+# the floor exists for the elements that cancel to near zero, and this bounds how many of them there may be, so a
+# regression that widens the cancellation errors shows up here first.  Per tensor, about 1.5 x the largest share
+# measured over all GPU parity cases; tensors not listed admit none.  One element is always admitted (a tensor of
+# 64 elements cannot express a share below 1/64).
+STRICT_FRAC_MAX = {
+    "bf16": {"logits": 0.038, "dW_a": 0.07, "dW_c": 0.055, "dW_out": 0.0022, "d_h_dec": 0.0015, "d_h_enc": 0.0001,
+             "dW_ih": 0.047, "dW_hh": 0.015, "db": 0.05},
+    "f32": {"ctx": 0.0008, "h_c": 0.0005, "logits": 0.0013, "dW_a": 0.006, "dW_c": 0.0012, "dW_out": 0.005,
+            "d_h_dec": 0.0026, "d_h_enc": 0.0021, "dW_ih": 0.004, "dW_hh": 0.0045, "db": 0.003, "y": 0.0009,
+            "hT": 0.0038, "cT": 0.0038, "dh0": 0.0053, "dc0": 0.0053, "dx": 0.001},
+}
+
+
+def strict_allowed(dtype, name, size):
+    """Number of elements of tensor `name` that may lie outside the floor-less rule."""
+    base = name.split(" ")[-1] if name.split(" ")[0] in ("decoder", "encoder") else name.split(" ")[0]
+    base = base.split("[")[0]
+    return max(1.0, STRICT_FRAC_MAX[dtype].get(base, 0.0) * size)
+
+# every assert_close of the session: (test id, tensor, storage type, statistics); written out by conftest.py
+# when ASX_PARITY_LOG names a file
+STATS_LOG = []
 
 
 def oracle_args(inp):
@@ -125,25 +156,32 @@ def err_stats(x, o, dtype):
         scale = np.sqrt(np.mean(o * o, axis=-1, keepdims=True))
     else:
         scale = np.sqrt(np.mean(o * o)) if o.size else 0.0
-    tol = atol + rtol * np.maximum(ao, scale) + 1e-300
+    tol = atol + rtol * np.maximum(ao, FLOOR[dtype] * scale) + 1e-300
     strict = d / (atol + rtol * ao + 1e-300)
+    # smallest floor (as a fraction of the row RMS) under which every element would still pass
+    need = np.where(strict > 1, (d - atol) / (rtol * np.maximum(scale, 1e-300)), 0.0)
     on = float(np.linalg.norm(o))
     dn = float(np.linalg.norm(x - o))
     return dict(ratio=float((d / tol).max()) if d.size else 0.0,
                 strict_frac=float((strict > 1).mean()) if d.size else 0.0,
+                strict_count=int((strict > 1).sum()) if d.size else 0,
+                floor_needed=float(need.max()) if d.size else 0.0,
                 norm=dn / on if on > 0 else dn, norm_tol=rtol,
-                maxabs=float(d.max()) if d.size else 0.0)
+                maxabs=float(d.max()) if d.size else 0.0, size=int(d.size))
 
 
 def assert_close(x, o, dtype, name, log=None):
     s = err_stats(x, o, dtype)
     if log is not None:
         log[name] = s
+    STATS_LOG.append(dict(test=os.environ.get("PYTEST_CURRENT_TEST", ""), name=name, dtype=dtype, **s))
     assert np.all(np.isfinite(np.asarray(x, dtype=np.float64))), f"{name}: non-finite values"
     assert s["ratio"] <= 1.0, f"{name}: elementwise tolerance exceeded {s}"
     on = float(np.linalg.norm(np.asarray(o, dtype=np.float64)))
     if on > 0:
         assert s["norm"] <= s["norm_tol"], f"{name}: norm-wise tolerance exceeded {s}"
+    assert s["strict_count"] <= strict_allowed(dtype, name, s["size"]), \
+        f"{name}: too many elements need the row-scale floor {s}"
     return s
 
 

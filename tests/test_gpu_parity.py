@@ -227,17 +227,49 @@ def _sample_sentences(B, seed):
     return sorted(fixed + rest)
 
 
+_WHOLE_BATCH = {}
+
+
+def _oracle_whole_batch(inp, chunks=8):
+    """The oracle's backward pass over the whole batch of a full-size configuration (once per configuration,
+    both row modes share it): every gradient, the weight gradients accumulated over all sentences as section
+    3.2 describes.  Run in chunks of sentences so that a line of progress appears between them."""
+    import sys
+    if inp.name in _WHOLE_BATCH:
+        return _WHOLE_BATCH[inp.name]
+    _WHOLE_BATCH.clear()                       # one configuration at a time: stress holds 2 GB of dW_out alone
+    total = None
+    step = (inp.B + chunks - 1) // chunks
+    for c, b0 in enumerate(range(0, inp.B, step)):
+        part = orc_backward(inp, list(range(b0, min(b0 + step, inp.B))))
+        if total is None:
+            total = part
+        else:
+            for k in total:
+                total[k] += part[k]            # per-sentence arrays are zero outside the chunk's sentences
+        sys.__stderr__.write(f"[oracle {inp.name}: sentences {min(b0 + step, inp.B)}/{inp.B}]\n")
+        sys.__stderr__.flush()
+    _WHOLE_BATCH[inp.name] = total
+    return total
+
+
+def orc_backward(inp, sentences):
+    return pu.orc.backward(*pu.oracle_args(inp), grad_scale=inp.grad_scale, sentences=sentences)
+
+
 @SKIP
 @pytest.mark.parametrize("name", ["mid", "large", "stress"])
 def test_full_size_config_sampled(name, skip):
     """The configuration at its full size, as the benchmark launches it.
 
-    Per-sentence results (alpha, ctx, h_c, logits, loss, argmax, d_h_dec,
-    d_h_enc) are compared for 8 sampled sentences against the oracle.  Weight
-    gradients sum over the batch: the 8 sentences are run as a batch of their
-    own (same H, V, tile configuration of the vocabulary GEMMs) and compared
-    in full, and the full batch must equal the sum of GPU shards.  The rest is
-    checked through properties that hold at any size."""
+    Per-sentence forward results (alpha, ctx, h_c, logits, loss, argmax) are
+    compared for 8 sampled sentences against the oracle, and those sentences
+    are also run as a batch of their own and compared in full.  All six
+    gradients of the full batch, as the timed launch configuration computes
+    them, are compared element by element with the oracle run over the whole
+    batch (mid and large in both row modes, stress in the mode the benchmark
+    times); the full batch must also equal the sum of GPU shards.  The rest
+    is checked through properties that hold at any size."""
     inp = make_inputs(name)
     idx = _sample_sentences(inp.B, 7)
     sub = inp.take_sentences(idx)
@@ -287,6 +319,15 @@ def test_full_size_config_sampled(name, skip):
     # (3) additivity: full batch == sum over 4 GPU shards (fp32 summation order only)
     full = {k: getattr(db, k).double().cpu().numpy() for k in ("dW_a", "dW_c", "db_out")}
     dW_out_full = db.dW_out.double()
+    if name != "stress" or skip:
+        # (2b) every gradient of the timed launch configuration against the oracle over the whole batch
+        gw = _oracle_whole_batch(inp)
+        for k in ("dW_a", "dW_c", "db_out"):
+            pu.assert_close(full[k], gw[k], inp.dtype, k + " (whole batch)", log)
+        pu.assert_close(pu._host(db.dW_out), gw["dW_out"], inp.dtype, "dW_out (whole batch)", log)
+        pu.assert_close(pu._host(db.d_h_dec), gw["d_h_dec"], inp.dtype, "d_h_dec (whole batch)", log)
+        pu.assert_close(pu._host(db.d_h_enc), gw["d_h_enc"], inp.dtype, "d_h_enc (whole batch)", log)
+        del gw
     acc = {k: np.zeros_like(v) for k, v in full.items()}
     acc_out = torch.zeros_like(dW_out_full)
     del run, db
