@@ -128,6 +128,31 @@ as_status attn_softmax_fwd(const as_shape* shape,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * attn_softmax_fwd for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight scoring / decoding loops (T = 1 per call), harnesses that forbid hipMalloc.  Same inputs,
+ * outputs, arithmetic and kernels as attn_softmax_fwd; the workspace is a 64 MiB array the library's code object
+ * holds on every GPU it runs on (AS_STATIC_SCRATCH_BYTES), so there is no workspace argument, no saved activation
+ * can be viewed afterwards and no backward pass can follow.  The call allocates and frees nothing.
+ *   - A shape whose attn_softmax_workspace_bytes() exceeds AS_STATIC_SCRATCH_BYTES is rejected with
+ *     AS_ERR_WORKSPACE before any launch (the paper's model size, S = 50, H = 1024, V = 32000 in bf16, fits up
+ *     to N = T*B = 256 positions per call: one decoder step of 256 sentences, two of 128).
+ *   - The calling thread's current device must be the one hip_stream belongs to.  The first call on a device
+ *     looks the array's address up (not a capturable operation): make one call outside graph capture first.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (nothing in it
+ *     needs to start at zero: every region is written before it is read).  Calls that overlap on one GPU,
+ *     on different streams or from different threads, race; order them on one stream.
+ * Errors otherwise as attn_softmax_fwd.
+ */
+#define AS_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+as_status attn_softmax_fwd_static(const as_shape* shape,
+                                  const void* h_dec, const void* h_enc, const int32_t* src_len,
+                                  const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                                  const int32_t* targets,
+                                  float* loss_sum, int32_t* n_tok,
+                                  float* tok_loss, int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask,
+                                  void* hip_stream);
+
+/*
  * Backward pass of grad_scale * loss_sum.  Takes the inputs of the forward
  * call and the workspace exactly as that call left it; overwrites (does not
  * accumulate into) the six float gradient outputs, all required:

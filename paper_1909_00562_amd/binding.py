@@ -23,7 +23,8 @@ STATUS_NAMES = {0: "AS_OK", 1: "AS_ERR_NULL", 2: "AS_ERR_SHAPE", 3: "AS_ERR_DTYP
 STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "gemm_logits",
                "xent_stats", "xent_dlogits", "gemm_dwout", "gemm_dhc", "gemm_dwc", "gemm_dch",
                "attn_bwd", "attn_softmax_bwd", "gemm_dwa", "gemm_dh", "misc", "adam", "compact"]
-EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_bwd", "attn_softmax_view",
+AS_STATIC_SCRATCH_BYTES = 64 << 20
+EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_fwd_static", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
            "attn_softmax_profile_select",
            "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
@@ -73,6 +74,8 @@ def load_library():
     lib.attn_softmax_workspace_bytes.argtypes = [ctypes.POINTER(AsShape)]
     lib.attn_softmax_fwd.restype = ctypes.c_int
     lib.attn_softmax_fwd.argtypes = [ctypes.POINTER(AsShape)] + [vp] * 14 + [vp, sz, vp]
+    lib.attn_softmax_fwd_static.restype = ctypes.c_int
+    lib.attn_softmax_fwd_static.argtypes = [ctypes.POINTER(AsShape)] + [vp] * 14 + [vp]
     lib.attn_softmax_bwd.restype = ctypes.c_int
     lib.attn_softmax_bwd.argtypes = [ctypes.POINTER(AsShape)] + [vp] * 8 + [vp, sz] + [vp] * 6 + [vp]
     lib.attn_softmax_view.restype = ctypes.c_int
@@ -133,6 +136,18 @@ def attn_softmax_fwd(shape, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targe
         _ptr(h_dec), _ptr(h_enc), _ptr(src_len), _ptr(W_a), _ptr(W_c), _ptr(W_out), _ptr(b_out), _ptr(targets),
         _ptr(loss_sum), _ptr(n_tok), _ptr(tok_loss), _ptr(argmax), _ptr(attn_mask), _ptr(tgt_mask),
         _ptr(workspace), int(workspace_bytes), stream or None)
+    if check:
+        _check(rc)
+    return rc
+
+
+def attn_softmax_fwd_static(shape, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, loss_sum, n_tok,
+                            tok_loss, argmax, attn_mask, tgt_mask, stream=0, check=True) -> int:
+    """attn_softmax_fwd on the library's own static scratch (no workspace argument, nothing allocated)."""
+    rc = load_library().attn_softmax_fwd_static(
+        ctypes.byref(shape) if shape is not None else None,
+        _ptr(h_dec), _ptr(h_enc), _ptr(src_len), _ptr(W_a), _ptr(W_c), _ptr(W_out), _ptr(b_out), _ptr(targets),
+        _ptr(loss_sum), _ptr(n_tok), _ptr(tok_loss), _ptr(argmax), _ptr(attn_mask), _ptr(tgt_mask), stream or None)
     if check:
         _check(rc)
     return rc

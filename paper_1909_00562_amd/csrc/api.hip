@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "gemm.h"
@@ -239,6 +240,37 @@ as_status check_common(const as_shape* s, const void* h_dec, const void* h_enc, 
 
 }  // namespace
 
+// ---- library-owned scratch (attn_softmax_fwd_static) --------------------------------
+// The workspace of callers that cannot allocate: one array in the code object, so every GPU the library runs on
+// holds its own copy from module load until the process ends.  Host code never uses the array's name as an
+// address: the device address is looked up once per device and kept.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// device address of `scratch` on the calling thread's current device
+as_status static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(AS_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(AS_ERR_HIP, "device %d is outside the %d the library keeps scratch for", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail(AS_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255)) return fail(AS_ERR_HIP, "static scratch resolved to %p", p);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AS_OK;
+}
+}  // namespace
+
 // Eq. 4-6 from the context vectors on: shared by the batched forward pass and the per-step one.
 static as_status fwd_from_ctx(const as_shape* s, const Layout& L, char* w, const char* hd, const char* wc,
                               const void* W_out, const void* b_out, const int32_t* targets, float* loss_sum,
@@ -293,6 +325,13 @@ static as_status fwd_from_ctx(const as_shape* s, const Layout& L, char* w, const
   return AS_OK;
 }
 
+// the forward pass proper, on whatever workspace the entry point hands it
+static as_status fwd_impl(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                          const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                          const int32_t* targets, float* loss_sum, int32_t* n_tok, float* tok_loss,
+                          int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
 extern "C" {
 
 size_t attn_softmax_workspace_bytes(const as_shape* shape) {
@@ -333,6 +372,37 @@ as_status attn_softmax_fwd(const as_shape* s, const void* h_dec, const void* h_e
                            const int32_t* targets, float* loss_sum, int32_t* n_tok, float* tok_loss,
                            int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
+  return fwd_impl(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, loss_sum, n_tok, tok_loss, argmax,
+                  attn_mask, tgt_mask, workspace, workspace_bytes, hip_stream);
+}
+
+as_status attn_softmax_fwd_static(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                                  const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                                  const int32_t* targets, float* loss_sum, int32_t* n_tok, float* tok_loss,
+                                  int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask, void* hip_stream) {
+  // everything checkable on the host first, with a stand-in workspace address that is never dereferenced
+  Layout L;
+  as_status rc = check_common(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets,
+                              reinterpret_cast<void*>(uintptr_t(256)), ~size_t(0), &L);
+  if (rc != AS_OK) return rc;
+  if (!loss_sum || !n_tok) return fail(AS_ERR_NULL, "loss_sum / n_tok is NULL");
+  if (L.total > kStaticScratchBytes)
+    return fail(AS_ERR_WORKSPACE, "this shape needs %zu bytes of workspace, the library's static scratch holds %zu: "
+                "use attn_softmax_fwd with a caller-owned workspace", L.total, kStaticScratchBytes);
+  void* ws = nullptr;
+  rc = static_scratch_ptr(&ws);
+  if (rc != AS_OK) return rc;
+  return fwd_impl(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, loss_sum, n_tok, tok_loss, argmax,
+                  attn_mask, tgt_mask, ws, kStaticScratchBytes, hip_stream);
+}
+
+}  // extern "C"
+
+static as_status fwd_impl(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
+                          const void* W_a, const void* W_c, const void* W_out, const void* b_out,
+                          const int32_t* targets, float* loss_sum, int32_t* n_tok, float* tok_loss,
+                          int32_t* argmax, uint8_t* attn_mask, uint8_t* tgt_mask, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
   Layout L;
   as_status rc = check_common(s, h_dec, h_enc, src_len, W_a, W_c, W_out, b_out, targets, workspace,
                               workspace_bytes, &L);
@@ -381,6 +451,8 @@ as_status attn_softmax_fwd(const as_shape* s, const void* h_dec, const void* h_e
   }
   return fwd_from_ctx(s, L, w, hd, wc, W_out, b_out, targets, loss_sum, n_tok, tok_loss, argmax, tgt_mask, st);
 }
+
+extern "C" {
 
 as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_enc, const int32_t* src_len,
                            const void* W_a, const void* W_c, const void* W_out, const void* b_out,

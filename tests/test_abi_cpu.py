@@ -229,3 +229,23 @@ def test_skip_pad_rows_is_validated_and_sizes_the_workspace():
     assert rc == 0 and n.value == s1.T * s1.B * 4 and ld.value == s1.B
     # the per-step entry points ignore the flag
     assert bd.attn_softmax_step_workspace_bytes(s1) == bd.attn_softmax_step_workspace_bytes(s0)
+
+
+def test_fwd_static_rejects_on_the_host_before_any_hip_call():
+    """The allocation-free forward entry point: argument errors and shapes beyond the library's static scratch
+    are turned away on the host (this runs without a GPU)."""
+    a = [0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 0x9000, 0xA000, None, None, None, None]
+    big = _shape(T=4, S=50, B=128, H=1024, V=32000, dtype=bd.AS_BF16)
+    assert bd.attn_softmax_workspace_bytes(big) > bd.AS_STATIC_SCRATCH_BYTES
+    assert bd.attn_softmax_fwd_static(big, *a, 0, check=False) == 4          # AS_ERR_WORKSPACE
+    assert "static scratch" in bd.attn_softmax_last_error()
+    assert bd.attn_softmax_fwd_static(None, *a, 0, check=False) == 1         # AS_ERR_NULL
+    ok = _shape(T=1, S=50, B=128, H=1024, V=32000, dtype=bd.AS_BF16)
+    assert bd.attn_softmax_workspace_bytes(ok) <= bd.AS_STATIC_SCRATCH_BYTES
+    b = list(a)
+    b[8] = None                                                              # loss_sum
+    assert bd.attn_softmax_fwd_static(ok, *b, 0, check=False) == 1
+    b = list(a)
+    b[0] = 0x1004                                                            # misaligned h_dec
+    assert bd.attn_softmax_fwd_static(ok, *b, 0, check=False) == 5           # AS_ERR_ALIGN
+    assert bd.attn_softmax_fwd_static(_shape(dtype=9), *a, 0, check=False) == 3
