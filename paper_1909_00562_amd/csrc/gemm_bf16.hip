@@ -1,28 +1,30 @@
 // bf16 x bf16 -> fp32 matrix products on the CDNA4 matrix cores (gfx950).
 //
-// One kernel template covers the three operand orientations the path needs
-// (both operands reduction-contiguous; B stored [K,N]; A and B stored [K,*]).
-// Whatever the orientation in memory, a block tile lands in LDS as rows of 64
-// reduction elements (128 bytes) whose 16-byte chunks are XOR-swizzled by the
-// row index (chunk ^ (row & 7) ^ ((row >> 3) & 1): 16 consecutive rows of one
-// chunk column land in 16 different 16-byte bank groups of the 64-bank LDS), so
-// tile writes and the 16-byte MFMA fragment reads are free of bank conflicts.
-//   * Reduction-contiguous operands go HBM -> LDS directly
-//     (buffer_load_dwordx4 ... lds): no staging registers, no ds_write.  The
-//     swizzle is applied on the global side: lane l of a wave-wide load fills
-//     LDS slot l of an 8-row group and fetches the chunk that belongs there.
-//   * Operands whose reduction index is the strided one are loaded 16 bytes
-//     along their contiguous index, transposed in registers (4 k-rows x 8
-//     columns per lane, v_perm_b32) and written with ds_write_b64.
-// Out-of-range rows / reduction indices are redirected to an offset beyond the
-// buffer resource's range, for which the hardware returns zeros: no branches.
-// The main loop is double buffered in LDS: the loads of tile k+1 are in flight
-// while the MFMAs of tile k run; one barrier per tile.
-//
-// Tiling: 256x256x64 block tile with 8 waves (2 x 4, two per SIMD, wave tile
-// 128x64) or 128x128x64 with 4 waves (wave tile 64x64); MFMA 32x32x16 bf16.
-// The epilogue stages each wave's accumulators through its own slice of LDS so
-// that global stores are 8/16-byte vectors along rows.
+// Three kernels, one operand description (GemmDev: up to six reduction segments, three
+// operand orientations: both reduction-contiguous; B stored [K,N]; A and B stored [K,*]):
+//   * gemm_bf16_pp_kernel: 256x256x64 block tile, 8 waves in two staggered groups, two
+//     LDS stages, persistent (one block per compute unit walks an XCD-partitioned list
+//     of work items as one stream of reduction tiles).  The large products.
+//   * gemm_bf16_ring_kernel: the same with 32-wide reduction sub-tiles in a ring of four
+//     LDS slots (three in flight).  The weight-gradient products (both operands strided
+//     in the reduction index).
+//   * gemm_bf16_kernel: 128x128x64 tile, 4 waves, one block per output tile, fragment reads
+//     software-pipelined inside a wave, split-K over multi-segment reductions.  Batched
+//     T x S attention products and small shapes.
+// Every operand goes HBM -> LDS directly (buffer_load_dwordx4 ... lds: no staging
+// registers, no ds_write) in the persistent kernels; the 128x128 kernel does the same for
+// reduction-contiguous operands and transposes strided ones in registers (v_perm_b32,
+// ds_write_b64).  Reduction-contiguous tiles are LDS rows of 64 reduction elements
+// (128 bytes) whose 16-byte chunks are XOR-swizzled by the row index
+// (chunk ^ (row & 7) ^ ((row >> 3) & 1): 16 consecutive rows of one chunk column land in
+// 16 different bank groups of the 64-bank LDS); the swizzle is applied on the global
+// side (lane l of a wave-wide load fills LDS slot l and fetches the chunk that belongs
+// there).  Strided tiles stay [k][256 columns] as in memory and are read with the
+// transposing ds_read_b64_tr_b16.  Out-of-range rows / reduction indices are redirected
+// to an offset beyond the buffer resource's range, which reads as zero: no branches.
+// MFMA 32x32x16 bf16 throughout; wave tile 128x64 (persistent kernels) or 64x64.
+// The epilogue stages each wave's accumulators through its own slice of LDS so that
+// global stores are 8/16-byte vectors along rows.
 #include "common.h"
 #include "gemm.h"
 
