@@ -18,7 +18,8 @@ roofline   = the kernel that takes the most time (a vocabulary GEMM): the flops 
              dense bf16 MFMA peak (2.5 PFLOP/s)
 roofline_hbm = the two streaming softmax-cross-entropy kernels against the 8 TB/s
              HBM peak (algorithmic bytes R*V*e for the statistics pass, 2*R*V*e for
-             the in-place dlogits pass)
+             the in-place dlogits pass); plain_stream_ceilings = plain read-only / copy /
+             in-place streams over the same bytes with the same grids (no arithmetic)
 cpu_baseline = the float64 numpy oracle timed on this machine's host cores on a few
              sentences of the same workload (a reported baseline, not a target)
 adam       = the fused Adam update of the four parameter tensors (outside the timed
@@ -62,14 +63,62 @@ GEMM_STAGES = {  # stage -> flops per launch; N = all positions, R = rows of the
 }
 
 
+def _source_digest(names):
+    """sha256 (16 hex digits) of each listed kernel source, as the traffic summary records them."""
+    import hashlib
+    out = {}
+    for n in names:
+        try:
+            with open(os.path.join(ROOT, "paper_1909_00562_amd", "csrc", n), "rb") as fh:
+                out[n] = hashlib.sha256(fh.read()).hexdigest()[:16]
+        except OSError:
+            out[n] = None
+    return out
+
+
 def _traffic_from_profiles(workload: str, stage: str):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summaries, if present."""
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if present AND taken with the kernel
+    sources as they are now (the summary records their digests): a counter figure of an older kernel is not
+    reported as this one's."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as fh:
-            return json.load(fh).get(workload, {}).get(stage)
+            prof = json.load(fh)
     except (OSError, ValueError):
         return None
+    rec = prof.get(workload, {}).get(stage)
+    if rec is None:
+        return None
+    want = prof.get("_sources", {})
+    if not want or _source_digest(sorted(want)) != want:
+        return None
+    return dict(rec, profile_commit=prof.get("_commit"))
+
+
+def stream_ceilings(lib, torch, rows, V, e, iters=5):
+    """What this machine's memory system gives plain streams over the bytes the cross-entropy kernels move
+    (attn_softmax_stream_probe: same grids and loads in flight, no arithmetic): read-only, copy, in-place
+    read-modify-write, GB/s by HIP events on the launch stream."""
+    row_bytes = (V * e + 15) // 16 * 16
+    nbytes = rows * row_bytes
+    dev = torch.device("cuda:0")
+    a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    a.fill_(1)
+    st = int(torch.cuda.current_stream().cuda_stream)
+    out = {"bytes": nbytes}
+    for kind, name, moved in ((0, "read_only", nbytes), (1, "copy", 2 * nbytes), (2, "in_place", 2 * nbytes)):
+        lib.attn_softmax_stream_probe(kind, a, b, rows, row_bytes, st)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            lib.attn_softmax_stream_probe(kind, a, b, rows, row_bytes, st)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        out[name] = {"ms": ms, "GB/s": moved / (ms * 1e-3) / 1e9, "frac_of_peak": moved / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    del a, b
+    return out
 
 
 def cpu_baseline(inp, budget_s: float = 40.0):
@@ -401,6 +450,8 @@ def main():
     del adam_state
     del db
     torch.cuda.empty_cache()
+    if roofline_hbm is not None:     # the same bytes as plain streams: this box's ceilings next to the kernels' figures
+        roofline_hbm["plain_stream_ceilings"] = stream_ceilings(lib, torch, R, V, e)
     out["per_step"] = per_step_probe(lib, torch)
     out["lstm_stack"] = lstm_probe(lib, torch)
     if not a.no_cpu_baseline:

@@ -220,6 +220,19 @@ as_status attn_softmax_profile_select(uint64_t stage_mask);
 as_status attn_softmax_profile_read(double* ms_total, int64_t* launches);
 
 /*
+ * Measurement aid for benchmarks: plain streaming kernels with the access patterns of the two softmax
+ * cross-entropy kernels (Eq. 5-6) and none of their arithmetic, to measure what this GPU's memory system gives
+ * such a stream.  `rows` chunks of `row_bytes` bytes each (a multiple of 16, one logits row), device memory:
+ *   kind 0  read-only: one block per row, eight 16-byte streaming loads in flight per thread (the statistics
+ *           kernel's pattern); buf2 receives 4 * rows uint32 words (so that the loads cannot be dropped)
+ *   kind 1  copy buf -> buf2 (rows * row_bytes bytes), the dlogits kernel's grid and loads in flight
+ *   kind 2  in-place read-modify-write of buf (each 16-bit element's sign bit flipped), same grid
+ * Errors: AS_ERR_NULL, AS_ERR_SHAPE, AS_ERR_ALIGN, AS_ERR_HIP.
+ */
+as_status attn_softmax_stream_probe(int kind, void* buf, void* buf2, int32_t rows, size_t row_bytes,
+                                    void* hip_stream);
+
+/*
  * Per-step mode: one decoder step (T = 1) at a time, for decoding, scoring and the
  * input-feeding variant of the model (section 4, "HybridNMTIF": the attentional
  * state of step t is an input of step t+1, so the steps cannot be batched).
@@ -235,6 +248,10 @@ as_status attn_softmax_profile_read(double* ms_total, int64_t* launches);
  * The workspace (attn_softmax_step_workspace_bytes) must not be used by another
  * call between prepare and the steps that follow it.  Dropout applies as in
  * attn_softmax_fwd when shape->dropout_p > 0.  Errors as attn_softmax_fwd.
+ * The step entry points are forward-only: attn_softmax_step_fwd does not save what the backward products read
+ * (Q = h_t W_a and the storage-type copies of the attention weights), so attn_softmax_bwd must NOT be called on
+ * a workspace a step left.  Per-step training (the input-feeding variant) runs attn_softmax_fwd with T = 1
+ * followed by attn_softmax_bwd with the same shape (same skip_pad_rows in both calls).
  */
 size_t attn_softmax_step_workspace_bytes(const as_shape* shape);
 as_status attn_softmax_step_prepare(const as_shape* shape, const void* h_enc, const void* W_a,

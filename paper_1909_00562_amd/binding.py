@@ -26,7 +26,7 @@ STAGE_NAMES = ["gemm_q", "attn_score", "attn_softmax", "attn_ctx", "gemm_hc", "g
 AS_STATIC_SCRATCH_BYTES = 64 << 20
 EXPORTS = ["attn_softmax_workspace_bytes", "attn_softmax_fwd", "attn_softmax_fwd_static", "attn_softmax_bwd", "attn_softmax_view",
            "attn_softmax_last_error", "attn_softmax_profile_enable", "attn_softmax_profile_read",
-           "attn_softmax_profile_select",
+           "attn_softmax_profile_select", "attn_softmax_stream_probe",
            "attn_softmax_adam_step", "attn_softmax_step_workspace_bytes", "attn_softmax_step_prepare",
            "attn_softmax_step_fwd", "lstm_stack_workspace_bytes", "lstm_stack_fwd", "lstm_stack_bwd"]
 
@@ -89,6 +89,8 @@ def load_library():
     lib.attn_softmax_profile_select.argtypes = [ctypes.c_uint64]
     lib.attn_softmax_profile_read.restype = ctypes.c_int
     lib.attn_softmax_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.attn_softmax_stream_probe.restype = ctypes.c_int
+    lib.attn_softmax_stream_probe.argtypes = [ctypes.c_int, vp, vp, ctypes.c_int32, sz, vp]
     lib.attn_softmax_step_workspace_bytes.restype = sz
     lib.attn_softmax_step_workspace_bytes.argtypes = [ctypes.POINTER(AsShape)]
     lib.attn_softmax_step_prepare.restype = ctypes.c_int
@@ -237,6 +239,14 @@ def lstm_stack_bwd(shape, x, lengths, W_ih, W_hh, dy, dhT, dcT, workspace, works
                                        *[a[0] if a else None for a in ins], _ptr(dy), _ptr(dhT), _ptr(dcT),
                                        _ptr(workspace), int(workspace_bytes), _ptr(dx),
                                        *[a[0] if a else None for a in outs], _ptr(dh0), _ptr(dc0), stream or None)
+    if check:
+        _check(rc)
+    return rc
+
+
+def attn_softmax_stream_probe(kind: int, buf, buf2, rows: int, row_bytes: int, stream=0, check=True) -> int:
+    rc = load_library().attn_softmax_stream_probe(int(kind), _ptr(buf), _ptr(buf2), int(rows), int(row_bytes),
+                                                  stream or None)
     if check:
         _check(rc)
     return rc

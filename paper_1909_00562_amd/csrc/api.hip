@@ -699,6 +699,16 @@ as_status attn_softmax_adam_step(const as_adam* hp, size_t n, const float* grad,
   return AS_OK;
 }
 
+as_status attn_softmax_stream_probe(int kind, void* buf, void* buf2, int32_t rows, size_t row_bytes, void* hip_stream) {
+  if (!buf || ((kind == 0 || kind == 1) && !buf2)) return fail(AS_ERR_NULL, "a required pointer is NULL");
+  if (kind < 0 || kind > 2 || rows < 1 || row_bytes < 16 || (row_bytes & 15) || row_bytes > ((size_t)1 << 31))
+    return fail(AS_ERR_SHAPE, "bad stream probe arguments kind=%d rows=%d row_bytes=%zu", kind, rows, row_bytes);
+  if (!aligned16(buf) || (buf2 && !aligned16(buf2))) return fail(AS_ERR_ALIGN, "pointer not 16-byte aligned");
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  AS_TRY(AS_STAGE_MISC, launch_stream_probe(kind, buf, buf2, rows, row_bytes, st));
+  return AS_OK;
+}
+
 as_status attn_softmax_profile_enable(int enable) {
   // drop whatever is pending
   for (auto& r : g_prof.pending) {

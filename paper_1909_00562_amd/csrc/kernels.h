@@ -107,6 +107,11 @@ hipError_t launch_lstm_step_bwd(const LstmStepBwd& p, hipStream_t st);
 // W_hh [4H,H] of one layer into the fragment-major form the forward (backward = false) or backward step reads
 hipError_t launch_ls_wfrag(const void* W_hh, void* dst, int H, bool backward, hipStream_t st);
 
+// Measurement aid: plain streams over `rows` chunks of `row_bytes` bytes (a multiple of 16).  kind 0: read-only with
+// the statistics kernel's load pattern, buf2 receives 4 words per row; kind 1: copy buf -> buf2 and kind 2:
+// in-place read-modify-write of buf, both with the dlogits kernel's grid and loads in flight.
+hipError_t launch_stream_probe(int kind, void* buf, void* buf2, int rows, size_t row_bytes, hipStream_t st);
+
 // Adam, bias corrections passed as inv_bc1 = 1 / (1 - beta1^step), inv_bc2 likewise; wout optional.
 hipError_t launch_adam_step(size_t n, const float* grad, float* master, float* m, float* v, void* wout,
                             bool out_bf16, float lr, float beta1, float beta2, float eps, float inv_bc1,
