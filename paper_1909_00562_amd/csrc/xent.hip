@@ -3,6 +3,8 @@
 // sum-exp, target logit, argmax) and an in-place pass that turns the stored
 // logits into dlogits = g*(p - onehot) while summing the columns for db_out.
 // Both passes are pure HBM streams: 16-byte loads/stores, fp32 arithmetic.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -61,9 +63,15 @@ __device__ __forceinline__ RowStat combine(const RowStat& a, const RowStat& b) {
   return r;
 }
 
-// UNR loads in flight per thread, NT = streaming loads.  Measured on 12288 x 128000 bf16: (1, false) 4.3 TB/s,
-// (4, true) 5.6, (8, true) 5.8; a pure read stream reaches 6.0-7.2 depending on the grid.
-template <typename TE, int UNR = 8, bool NT = true>
+// UNR loads in flight per thread, all streaming (4 to 8 in flight measure the same).  A plain read stream with the
+// same grid and loads moves 6.8 TB/s on this part when it runs alone; the first form of this kernel, which updated
+// the running maximum and its index per element, reached 5.4 inside the step, this one 5.7: a wave's
+// vector instruction occupies its 16-lane SIMD for four cycles, so every operation per element counts.  Per
+// element this form spends: one shift / mask to widen bf16, half a v_max3, one fused multiply-add into the base-2
+// exponent, one v_exp_f32, one add.  The running maximum is updated once per group of UNR vectors instead of per
+// vector, and the arg max is tracked at vector granularity (column of the first vector of the thread that attains
+// the maximum); the element inside that vector is found once per row by re-reading 16 bytes.
+template <typename TE, int UNR = 8>
 __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ logits, int64_t ldV, int V,
                                                         const int32_t* __restrict__ targets, int pad_id,
                                                         float* __restrict__ lse, float* __restrict__ tok_loss_ws,
@@ -72,47 +80,78 @@ __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ 
                                                         const int32_t* __restrict__ rows,
                                                         const int32_t* __restrict__ n_act) {
   constexpr int VEC = Vec<TE>::N;
+  constexpr float L2E = 1.4426950408889634f;
+  constexpr uint32_t NEG_INF_WORD = sizeof(TE) == 2 ? 0xff80ff80u : 0xff800000u;   // -inf in every element
   // compacted rows (rows != null): logits row r belongs to position rows[r]; lse and the workspace loss are
   // indexed by r, the caller's per-position outputs by the position
   const int n = blockIdx.x, tid = threadIdx.x;
   if (rows && n >= *n_act) return;
   const int pos = rows ? rows[n] : n;
   const TE* x = logits + (int64_t)n * ldV;
-  RowStat st{-INFINITY, 0.f, 0x7fffffff};
-  // UNR independent 16-byte loads per thread are issued before any of them is used: a row is read once, so
-  // the only way to cover the memory latency is to have enough bytes in flight per compute unit
-  for (int v0 = tid * VEC; v0 < V; v0 += 256 * VEC * UNR) {
+  RowStat st{-INFINITY, 0.f, 0x7fffffff};   // idx: column of the first element of the vector holding the first maximum
+  // one group = UNR vectors of this thread, 256 * VEC columns apart; GUARD: the group may reach past the row
+  auto group = [&](int v0, auto guard) {
+    constexpr bool GUARD = decltype(guard)::value;
+    // UNR independent 16-byte loads per thread are issued before any of them is used: a row is read once, so
+    // the only way to cover the memory latency is to have enough bytes in flight per compute unit
     uint4 q[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       const int v = v0 + u * 256 * VEC;
-      q[u] = make_uint4(0, 0, 0, 0);
-      if (v < V) q[u] = NT ? ld16_stream(x + v) : *reinterpret_cast<const uint4*>(x + v);
+      if constexpr (GUARD) {
+        q[u] = make_uint4(NEG_INF_WORD, NEG_INF_WORD, NEG_INF_WORD, NEG_INF_WORD);   // a vector past the row: all -inf
+        if (v < V) q[u] = ld16_stream(x + v);
+      } else {
+        q[u] = ld16_stream(x + v);
+      }
     }
+    float f[UNR][VEC], vm[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
       const int v = v0 + u * 256 * VEC;
-      if (v >= V) break;
-      float f[VEC];
-      unpack<TE>(q[u], f);
-      float vm = -INFINITY;
-      int vi = 0;
+      unpack<TE>(q[u], f[u]);
+      if constexpr (GUARD) {
+        if (v < V && v + VEC > V) {           // the one ragged vector of a row whose length is not a multiple of VEC
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) {
-        if (v + i >= V) f[i] = -INFINITY;
-        if (f[i] > vm) { vm = f[i]; vi = i; }     // strict: first (lowest) index wins
+          for (int i = 0; i < VEC; ++i)
+            if (v + i >= V) f[u][i] = -INFINITY;
+        }
       }
-      if (vm > st.m) {
-        st.s *= __expf(st.m - vm);                  // exp(-inf) = 0 on the first vector
-        st.m = vm;
-        st.idx = v + vi;
-      }
-      float e = 0.f;
+      float a = f[u][0];
 #pragma unroll
-      for (int i = 0; i < VEC; ++i) e += __expf(f[i] - st.m);
-      st.s += e;
+      for (int i = 1; i + 1 < VEC; i += 2) a = fmaxf(fmaxf(a, f[u][i]), f[u][i + 1]);   // v_max3_f32
+      if constexpr (VEC % 2 == 0) a = fmaxf(a, f[u][VEC - 1]);
+      vm[u] = a;
     }
-  }
+    float gm = fmaxf(fmaxf(vm[0], vm[1]), vm[2]);
+#pragma unroll
+    for (int u = 3; u + 1 < UNR; u += 2) gm = fmaxf(fmaxf(gm, vm[u]), vm[u + 1]);
+    if constexpr (UNR % 2 == 0) gm = fmaxf(gm, vm[UNR - 1]);
+    if (gm > st.m) {                          // strict: an equal maximum further right does not move the arg max
+      st.s *= __builtin_amdgcn_exp2f((st.m - gm) * L2E);   // exp2(-inf) = 0 the first time
+      st.m = gm;
+      int first = 0;
+#pragma unroll
+      for (int u = UNR - 1; u >= 0; --u)      // lowest u (= lowest column of this thread) attaining gm
+        if (vm[u] == gm) first = u;
+      st.idx = v0 + first * 256 * VEC;
+    }
+    const float mb = -st.m * L2E;
+    float e0 = 0.f, e1 = 0.f;                 // two chains: the adds do not wait on each other
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+#pragma unroll
+      for (int i = 0; i < VEC; i += 2) {
+        e0 += __builtin_amdgcn_exp2f(__builtin_fmaf(f[u][i], L2E, mb));
+        e1 += __builtin_amdgcn_exp2f(__builtin_fmaf(f[u][i + 1], L2E, mb));
+      }
+    st.s += e0 + e1;
+  };
+  static_assert(UNR >= 3, "group maximum is taken with v_max3");
+  constexpr int STEP = 256 * VEC * UNR;
+  int v0 = tid * VEC;
+  for (; v0 + (UNR - 1) * 256 * VEC + VEC <= V; v0 += STEP) group(v0, std::false_type{});
+  if (v0 < V) group(v0, std::true_type{});
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     RowStat other;
@@ -126,6 +165,18 @@ __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ 
   __syncthreads();
   if (tid == 0) {
     RowStat r = combine(combine(ws[0], ws[1]), combine(ws[2], ws[3]));
+    // the vectors of a row are disjoint column ranges, so the lowest vector column among equal maxima holds the
+    // lowest arg max; find the element inside it
+    int amax = 0;
+    if (r.idx < V) {
+      float f[VEC];
+      unpack<TE>(*reinterpret_cast<const uint4*>(x + r.idx), f);
+      int k = VEC - 1;
+#pragma unroll
+      for (int i = VEC - 1; i >= 0; --i)
+        if (r.idx + i < V && f[i] == r.m) k = i;
+      amax = r.idx + k;
+    }
     const float l = r.m + logf(r.s);
     const int y = targets[pos];
     const bool nonpad = (y != pad_id) && (y >= 0) && (y < V);
@@ -133,7 +184,7 @@ __global__ __launch_bounds__(256) void xent_stats_kernel(const TE* __restrict__ 
     lse[n] = l;
     tok_loss_ws[n] = loss;
     if (tok_loss) tok_loss[pos] = loss;
-    if (argmax) argmax[pos] = r.idx;
+    if (argmax) argmax[pos] = amax;
     if (tgt_mask) tgt_mask[pos] = nonpad ? 1 : 0;
   }
 }
