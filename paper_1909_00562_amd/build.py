@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libattn_softmax.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "attn_rows.hip", "xent.hip", "adam.hip", "attn_step.hip", "compact.hip", "lstm.hip", "lstm_step.hip", "stream_probe.hip"]
+SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "attn_rows.hip", "xent.hip", "adam.hip", "attn_step.hip", "compact.hip", "lstm.hip", "lstm_step.hip", "stream_probe.hip", "attn_fused.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

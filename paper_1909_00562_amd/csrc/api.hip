@@ -426,28 +426,35 @@ static as_status fwd_impl(const as_shape* s, const void* h_dec, const void* h_en
     g.C_lo = w + L.q_lo;
     AS_TRY(AS_STAGE_GEMM_Q, launch_gemm(g, bf, L.p_q.big_tile, st));
   }
-  {  // score[b] = Q_b h_enc_b^T, one product per sentence                  (Eq. 2)
-    GemmArgs g;
-    g.seg(w + L.q, BH, H, he, BH, H, H);
-    g.seg(w + L.q_lo, BH, H, he, BH, H, H);
-    g.a_kc = true; g.b_kc = true;
-    g.M = T; g.N = S; g.batch = B;
-    g.C = w + L.scores; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
-    AS_TRY(AS_STAGE_ATTN_SCORE, launch_gemm(g, bf, L.p_score.big_tile, st));
-  }
-  AS_TRY(AS_STAGE_ATTN_SOFTMAX,                                        // Eq. 1
-         launch_attn_softmax_rows(reinterpret_cast<const float*>(w + L.scores), src_len, B, T, S,
-                                  reinterpret_cast<float*>(w + L.alpha32), w + L.alphaE,
-                                  w + L.alphaE_lo, L.ldS, bf, attn_mask, st));
-  {  // ctx_b = alpha_b h_enc_b                                            (Eq. 3)
-    GemmArgs g;
-    g.seg(w + L.alphaE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
-    g.seg(w + L.alphaE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
-    g.a_kc = true; g.b_kc = false;
-    g.M = T; g.N = H; g.batch = B;
-    g.C = w + L.ctx; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
-    g.C_lo = w + L.ctx_lo;
-    AS_TRY(AS_STAGE_ATTN_CTX, launch_gemm(g, bf, L.p_ctx.big_tile, st));
+  if (bf && attn_fwd_fused_supported(S, H)) {
+    // Eq. 2 (second half), 1 and 3 in one kernel per (sentence, 32 decoder steps): the scores stay on chip
+    AS_TRY(AS_STAGE_ATTN_SCORE,
+           launch_attn_fwd_fused(w + L.q, w + L.q_lo, he, src_len, B, T, S, H, reinterpret_cast<float*>(w + L.alpha32),
+                                 w + L.alphaE, w + L.alphaE_lo, L.ldS, w + L.ctx, w + L.ctx_lo, attn_mask, st));
+  } else {
+    {  // score[b] = Q_b h_enc_b^T, one product per sentence                  (Eq. 2)
+      GemmArgs g;
+      g.seg(w + L.q, BH, H, he, BH, H, H);
+      g.seg(w + L.q_lo, BH, H, he, BH, H, H);
+      g.a_kc = true; g.b_kc = true;
+      g.M = T; g.N = S; g.batch = B;
+      g.C = w + L.scores; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
+      AS_TRY(AS_STAGE_ATTN_SCORE, launch_gemm(g, bf, L.p_score.big_tile, st));
+    }
+    AS_TRY(AS_STAGE_ATTN_SOFTMAX,                                        // Eq. 1
+           launch_attn_softmax_rows(reinterpret_cast<const float*>(w + L.scores), src_len, B, T, S,
+                                    reinterpret_cast<float*>(w + L.alpha32), w + L.alphaE,
+                                    w + L.alphaE_lo, L.ldS, bf, attn_mask, st));
+    {  // ctx_b = alpha_b h_enc_b                                            (Eq. 3)
+      GemmArgs g;
+      g.seg(w + L.alphaE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+      g.seg(w + L.alphaE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+      g.a_kc = true; g.b_kc = false;
+      g.M = T; g.N = H; g.batch = B;
+      g.C = w + L.ctx; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
+      g.C_lo = w + L.ctx_lo;
+      AS_TRY(AS_STAGE_ATTN_CTX, launch_gemm(g, bf, L.p_ctx.big_tile, st));
+    }
   }
   return fwd_from_ctx(s, L, w, hd, wc, W_out, b_out, targets, loss_sum, n_tok, tok_loss, argmax, tgt_mask, st);
 }
@@ -539,27 +546,35 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
     g.C = d_h_dec; g.ldc = H; g.c_bf16 = false;
     AS_TRY(AS_STAGE_GEMM_DCH, launch_gemm(g, bf, L.p_dch.big_tile, st));
   }
-  {  // dalpha_b = dC_b h_enc_b^T
-    GemmArgs g;
-    g.seg(w + L.dC, BH, H, he, BH, H, H);
-    g.seg(w + L.dC_lo, BH, H, he, BH, H, H);
-    g.a_kc = true; g.b_kc = true;
-    g.M = T; g.N = S; g.batch = B;
-    g.C = w + L.dalpha; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
-    AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dalpha.big_tile, st));
-  }
-  AS_TRY(AS_STAGE_ATTN_SOFTMAX_BWD,
-         launch_attn_softmax_rows_bwd(reinterpret_cast<const float*>(w + L.alpha32),
-                                      reinterpret_cast<const float*>(w + L.dalpha), B, T, S, w + L.dscoreE,
-                                      w + L.dscoreE_lo, L.ldS, bf, st));
-  {  // dQ_b = dscore_b h_enc_b
-    GemmArgs g;
-    g.seg(w + L.dscoreE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
-    g.seg(w + L.dscoreE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
-    g.a_kc = true; g.b_kc = false;
-    g.M = T; g.N = H; g.batch = B;
-    g.C = w + L.dQ; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
-    AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dq.big_tile, st));
+  if (bf && attn_fwd_fused_supported(S, H)) {
+    // dalpha, the softmax Jacobian and dQ in one kernel per (sentence, 32 decoder steps): dalpha stays on chip
+    AS_TRY(AS_STAGE_ATTN_BWD,
+           launch_attn_bwd_fused(w + L.dC, w + L.dC_lo, he, src_len, B, T, S, H,
+                                 reinterpret_cast<const float*>(w + L.alpha32), w + L.dscoreE, w + L.dscoreE_lo, L.ldS,
+                                 w + L.dQ, st));
+  } else {
+    {  // dalpha_b = dC_b h_enc_b^T
+      GemmArgs g;
+      g.seg(w + L.dC, BH, H, he, BH, H, H);
+      g.seg(w + L.dC_lo, BH, H, he, BH, H, H);
+      g.a_kc = true; g.b_kc = true;
+      g.M = T; g.N = S; g.batch = B;
+      g.C = w + L.dalpha; g.ldc = S; g.sC = (int64_t)T * S; g.c_bf16 = false;
+      AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dalpha.big_tile, st));
+    }
+    AS_TRY(AS_STAGE_ATTN_SOFTMAX_BWD,
+           launch_attn_softmax_rows_bwd(reinterpret_cast<const float*>(w + L.alpha32),
+                                        reinterpret_cast<const float*>(w + L.dalpha), B, T, S, w + L.dscoreE,
+                                        w + L.dscoreE_lo, L.ldS, bf, st));
+    {  // dQ_b = dscore_b h_enc_b
+      GemmArgs g;
+      g.seg(w + L.dscoreE, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+      g.seg(w + L.dscoreE_lo, L.ldS, (int64_t)T * L.ldS, he, BH, H, S);
+      g.a_kc = true; g.b_kc = false;
+      g.M = T; g.N = H; g.batch = B;
+      g.C = w + L.dQ; g.ldc = BH; g.sC = H; g.c_bf16 = bf;
+      AS_TRY(AS_STAGE_ATTN_BWD, launch_gemm(g, bf, L.p_dq.big_tile, st));
+    }
   }
   {  // d_h_enc_b = alpha_b^T dC_b + dscore_b^T Q_b  (rows s >= src_len[b]: alpha = dscore = 0)
     GemmArgs g;

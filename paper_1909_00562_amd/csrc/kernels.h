@@ -20,6 +20,19 @@ hipError_t launch_attn_softmax_rows_bwd(const float* alpha32, const float* dalph
                                         void* dscoreE, void* dscoreE_lo, int64_t ldS, bool e_bf16,
                                         hipStream_t st);
 
+// Eq. 1-3 fused for the batched path, bf16 storage, S <= 128 (attn_fwd_fused_supported): q_hi / q_lo [T,B,H] (Q = h_dec
+// W_a as value and rounding remainder), h_enc [S,B,H] -> alpha32 [B,T,S], alphaE / alphaE_lo [B,T,ldS] (zero padded),
+// ctx / ctx_lo [T,B,H], optional attn_mask [B,S].  One workgroup per (sentence, 32 decoder steps).
+bool attn_fwd_fused_supported(int S, int H);
+hipError_t launch_attn_fwd_fused(const void* q_hi, const void* q_lo, const void* h_enc, const int32_t* src_len, int B,
+                                 int T, int S, int H, float* alpha32, void* alphaE, void* alphaE_lo, int64_t ldS,
+                                 void* ctx, void* ctx_lo, uint8_t* attn_mask, hipStream_t st);
+// First half of the attention backward pass with the same kernel: dC_hi / dC_lo [T,B,H], alpha32 [B,T,S] (read) ->
+// dscoreE / dscoreE_lo [B,T,ldS] (softmax Jacobian, zero padded) and dQ [T,B,H] = dscore . h_enc (value only).
+hipError_t launch_attn_bwd_fused(const void* dC_hi, const void* dC_lo, const void* h_enc, const int32_t* src_len,
+                                 int B, int T, int S, int H, const float* alpha32, void* dscoreE, void* dscoreE_lo,
+                                 int64_t ldS, void* dQ, hipStream_t st);
+
 // Row compaction (rows / n_act below, both null = off): logits, lse and tok_loss_ws hold only the *n_act rows
 // whose target is not padding, row r being position rows[r]; N stays the bound the launch is sized for.
 // Position n -> row_pos[n] (its compacted row, -1 at padding), the list rows[0 .. *n_act) of positions in
