@@ -56,7 +56,7 @@ GEMM_STAGES = {  # stage -> flops per launch; N = all positions, R = rows of the
     "gemm_dhc": lambda N, R, H, V: 2.0 * R * H * V,
     "gemm_q": lambda N, R, H, V: 2.0 * N * H * H,
     "gemm_hc": lambda N, R, H, V: 4.0 * N * H * H,
-    "gemm_dwc": lambda N, R, H, V: 2.0 * N * H * H,      # per launch (two launches per step)
+    "gemm_dwc": lambda N, R, H, V: 4.0 * N * H * H,      # both halves of dW_c in one launch
     "gemm_dch": lambda N, R, H, V: 2.0 * N * H * H,      # per launch (two launches per step)
     "gemm_dwa": lambda N, R, H, V: 2.0 * N * H * H,
     "gemm_dh": lambda N, R, H, V: 2.0 * N * H * H,

@@ -144,7 +144,7 @@ Layout make_layout(const as_shape* s) {
   // no longer fills whole rounds of the grid, so the kernel splits the reduction to fit the count it reads.
   L.dhc_dyn = s->skip_pad_rows != 0 && bf && L.p_dhc.big_tile;
   if (L.dhc_dyn && L.p_dhc.splits < 8) L.p_dhc.splits = 8;
-  L.p_dwc = gemm_plan(H, H, N, 1, bf, true);
+  L.p_dwc = gemm_plan(H, H, N, 2, bf, true);          // both halves of dW_c in one launch
   L.p_dch = gemm_plan(N, H, H, 1, bf, false);
   L.p_dalpha = gemm_plan(T, S, H, B, bf, false);
   L.p_dq = gemm_plan(T, H, S, B, bf, false);
@@ -156,7 +156,7 @@ Layout make_layout(const as_shape* s) {
   mx(gemm_partial_bytes(N, H, 1, L.p_hc.splits));
   mx(gemm_partial_bytes(V, H, 1, L.p_dwout.splits));
   mx(gemm_partial_bytes(N, H, 1, L.p_dhc.splits));
-  mx(gemm_partial_bytes(H, H, 1, L.p_dwc.splits));
+  mx(gemm_partial_bytes(H, H, 2, L.p_dwc.splits));
   mx(gemm_partial_bytes(H, H, 1, L.p_dwa.splits));
   L.partial_bytes = pb;
 
@@ -519,12 +519,15 @@ as_status attn_softmax_bwd(const as_shape* s, const void* h_dec, const void* h_e
   if (L.compact)   // dz back to its time-major rows, zeros at the padding rows: the rest of the pass is per sentence
     AS_TRY(AS_STAGE_COMPACT, launch_scatter_rows(reinterpret_cast<const int32_t*>(w + L.row_pos), N, w + L.dz_c,
                                                  w + L.dz, w + L.dz_lo_c, w + L.dz_lo, (int64_t)H * L.e, st));
-  for (int half = 0; half < 2; ++half) {  // dW_c = dz^T [ctx ; h_dec]
+  {  // dW_c = dz^T [ctx ; h_dec]: the two halves as one launch of two products that share dz; the second operand
+     // of half 1 is the caller's h_dec, reached from ctx through a "batch stride" that is just the distance
+     // between the two buffers (both 16-byte aligned, so it is a whole number of 8-element vectors)
     GemmArgs g;
-    g.seg(w + L.dz, H, 0, half == 0 ? (const void*)(w + L.ctx) : (const void*)hd, H, 0, N);
+    const int64_t h_dec_from_ctx = (hd - (w + L.ctx)) / (int64_t)L.e;
+    g.seg(w + L.dz, H, 0, w + L.ctx, H, h_dec_from_ctx, N);
     g.a_kc = false; g.b_kc = false;
-    g.M = H; g.N = H;
-    g.C = dW_c + (size_t)half * H; g.ldc = 2 * H; g.c_bf16 = false;
+    g.M = H; g.N = H; g.batch = 2;
+    g.C = dW_c; g.ldc = 2 * H; g.sC = H; g.c_bf16 = false;
     g.splits = L.p_dwc.splits; g.partial = partial;
     AS_TRY(AS_STAGE_GEMM_DWC, launch_gemm(g, bf, L.p_dwc.big_tile, st));
   }
