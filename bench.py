@@ -271,6 +271,10 @@ def main():
                          "non-pad ones")
     ap.add_argument("--no-stage-events", action="store_true",
                     help="do not bracket kernels with HIP events inside the timed region")
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed forward + backward steps: no HIP-graph replay, no per-step / LSTM / stream "
+                         "probes (for rocprofv3 --pmc runs, whose counter collection does not survive long graph "
+                         "replays)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy kernel (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -363,7 +367,7 @@ def main():
 
     # the same step replayed from a HIP graph (one capture of forward + backward): what the launches cost
     graph_ms = None
-    if not a.train_step:
+    if not a.train_step and not a.main_only:
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         db.sync()
@@ -450,11 +454,13 @@ def main():
     del adam_state
     del db
     torch.cuda.empty_cache()
-    if roofline_hbm is not None:     # the same bytes as plain streams: this box's ceilings next to the kernels' figures
+    if roofline_hbm is not None and not a.main_only:
+        # the same bytes as plain streams: this box's ceilings next to the kernels' figures
         roofline_hbm["plain_stream_ceilings"] = stream_ceilings(lib, torch, R, V, e)
-    out["per_step"] = per_step_probe(lib, torch)
-    out["lstm_stack"] = lstm_probe(lib, torch)
-    if not a.no_cpu_baseline:
+    if not a.main_only:
+        out["per_step"] = per_step_probe(lib, torch)
+        out["lstm_stack"] = lstm_probe(lib, torch)
+    if not a.no_cpu_baseline and not a.main_only:
         out["cpu_baseline"] = cpu_baseline(inp)
     print(json.dumps(out))
 
