@@ -28,6 +28,8 @@
 #include "common.h"
 #include "gemm.h"
 
+#include <type_traits>
+
 namespace asx {
 
 struct GemmDev {
@@ -163,13 +165,45 @@ __device__ __forceinline__ bf16x8_t frag_read(const unsigned char* base, int row
 // `region` is this wave's private LDS slice: CH rows of EP_LD floats (CH = 32 or 16).
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
+// Accumulators of one round (CH rows of the wave tile) -> the wave's staging slice.
+// MI16 = false: 32x32 MFMA tiles (register r of lane l: row 8*(r/4) + 4*(l/32) + r%4, column l%32).
+// MI16 = true: 16x16 tiles (register r of lane l: row 4*(l/16) + r, column l%16), one tile row per round; the four
+// lane groups of a store would hit the same 16 banks, so the 16-column block j of row group g is kept at block j ^ g.
+template <bool MI16, int TN, int CH, int EP_LD, typename AccT>
+__device__ __forceinline__ void stage_round(float* stage_f, AccT& acc, int ic, int lane) {
+  if constexpr (MI16) {
+    static_assert(CH == 16 && EP_LD == 64 && TN == 4, "one 16-row tile row per round, 64-column wave tile");
+    const int g = lane >> 4, c = lane & 15;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) stage_f[(4 * g + r) * 64 + (((j ^ g) & 3) << 4) + c] = acc[ic][j][r];
+  } else {
+    const int i = ic / (32 / CH), part = ic % (32 / CH);
+    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int trow = (r >> 2) * 8;
+        if (trow / CH != part) continue;
+        stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
+      }
+  }
+}
+// float offset of the 4-column vector (row group it, lane's vrow / vcol) inside the staging slice
+template <bool MI16, int EP_LD>
+__device__ __forceinline__ int stage_read_off(int it, int vrow, int vcol) {
+  return (it * 4 + vrow) * EP_LD + (MI16 ? (vcol ^ (it << 4)) : vcol);
+}
+
 // Vector form of the epilogue below for products whose destinations allow 8/16-byte
 // row vectors and whose N is a multiple of 4 (chosen on the host, per launch): stores (and the gate / accumulate
 // loads) go through buffer resources that start at the wave tile's first element, so
 // the row part of an address is a scalar offset, the lane part one register, and rows
 // beyond M are dropped by pointing the lane offset outside the resource instead of branching.
-template <int TM, int TN, bool OUT_BF16, bool DROP, int CH, int EP_LD>
-__device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x16_t (&acc)[TM][TN],
+template <int TM, int TN, bool OUT_BF16, bool DROP, int CH, int EP_LD, bool MI16, typename AccT>
+__device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, AccT& acc,
                                                   unsigned char* region, int lane, int row0, int col0, int batch,
                                                   int z) {
   constexpr int WAIT_LGKM_ONLY = 0xC07F;
@@ -205,31 +239,20 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x
     // them were most of the write-out time of the vocabulary projection (two waves share a SIMD's vector ALU).
     // The CH/4 reads of a round are in flight together, and the LDS writes of round ic+1 are issued when
     // the last read of round ic has returned, so their latency hides behind that row group's stores.
-    constexpr int NR = TM * (32 / CH);
-    auto write_round = [&](int ic) {
-      const int i = ic / (32 / CH), part = ic % (32 / CH);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int trow = (r >> 2) * 8;
-          if (trow / CH != part) continue;
-          stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
-        }
-    };
+    constexpr int NR = MI16 ? TM : TM * (32 / CH);
+    auto write_round = [&](int ic) { stage_round<MI16, TN, CH, EP_LD>(stage_f, acc, ic, lane); };
     write_round(0);
 #pragma unroll
     for (int ic = 0; ic < NR; ++ic) {
-      const int i = ic / (32 / CH), part = ic % (32 / CH);
       __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
       f32x4_t v4s[CH / 4];
 #pragma unroll
       for (int it = 0; it < CH / 4; ++it)
-        v4s[it] = *reinterpret_cast<const f32x4_t*>(stage_f + (it * 4 + vrow) * EP_LD + vcol);
+        v4s[it] = *reinterpret_cast<const f32x4_t*>(stage_f + stage_read_off<MI16, EP_LD>(it, vrow, vcol));
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int it = 0; it < CH / 4; ++it) {
-        const int nrow = i * 32 + part * CH + it * 4;            // tile row of the lane's row group (compile time)
+        const int nrow = ic * CH + it * 4;                       // tile row of the lane's row group (compile time)
         const bool in = nrow < rows_left && col_in;
         if (it == CH / 4 - 1) {
           __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
@@ -253,22 +276,14 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x
     return;
   }
 #pragma unroll
-  for (int ic = 0; ic < TM * (32 / CH); ++ic) {
-    const int i = ic / (32 / CH), part = ic % (32 / CH);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int trow = (r >> 2) * 8;
-        if (trow / CH != part) continue;
-        stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
-      }
+  for (int ic = 0; ic < (MI16 ? TM : TM * (32 / CH)); ++ic) {
+    stage_round<MI16, TN, CH, EP_LD>(stage_f, acc, ic, lane);
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
 #pragma unroll
     for (int it = 0; it < CH / 4; ++it) {
-      const int nrow = i * 32 + part * CH + it * 4;              // tile row of the lane's row group (compile time)
+      const int nrow = ic * CH + it * 4;                         // tile row of the lane's row group (compile time)
       const bool in = nrow < rows_left && col_in;
-      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + (it * 4 + vrow) * EP_LD + vcol);
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + stage_read_off<MI16, EP_LD>(it, vrow, vcol));
       const uint32_t row_el = (uint32_t)nrow * ld32;             // wave-uniform: goes into the scalar offset operand
       float v[4] = {v4[0] + bias4[0], v4[1] + bias4[1], v4[2] + bias4[2], v4[3] + bias4[3]};
       if (fuse && p.act_tanh) {
@@ -326,13 +341,14 @@ __device__ __forceinline__ void gemm_epilogue_vec(const GemmDev& p, int Mv, f32x
   }
 }
 
-template <int TM, int TN, bool OUT_BF16, bool VEC, bool DROP, int CH = 32, int EP_LD = 72>
-__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, int Mv, f32x16_t (&acc)[TM][TN],
+template <int TM, int TN, bool OUT_BF16, bool VEC, bool DROP, int CH = 32, int EP_LD = 72, bool MI16 = false,
+          typename AccT>
+__device__ __forceinline__ void gemm_epilogue(const GemmDev& p, int Mv, AccT& acc,
                                               unsigned char* region, int lane, int row0, int col0, int batch, int z) {
-  static_assert(TN == 2, "64-column wave tiles");
+  static_assert(TN == (MI16 ? 4 : 2), "64-column wave tiles");
   static_assert(CH == 32 || CH == 16, "chunk of one or half an MFMA tile");
   if constexpr (VEC) {
-    gemm_epilogue_vec<TM, TN, OUT_BF16, DROP, CH, EP_LD>(p, Mv, acc, region, lane, row0, col0, batch, z);
+    gemm_epilogue_vec<TM, TN, OUT_BF16, DROP, CH, EP_LD, MI16>(p, Mv, acc, region, lane, row0, col0, batch, z);
     return;
   }
   constexpr int WAIT_LGKM_ONLY = 0xC07F;   // leaves global loads in flight
@@ -348,23 +364,15 @@ __device__ __forceinline__ void gemm_epilogue(const GemmDev& p, int Mv, f32x16_t
       if (gcol + c < p.N) bias4[c] = bf16_bits_to_f32(p.bias[gcol + c]);
   }
 #pragma unroll
-  for (int ic = 0; ic < TM * (32 / CH); ++ic) {
-    const int i = ic / (32 / CH), part = ic % (32 / CH);   // MFMA tile row, chunk inside it
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int trow = (r >> 2) * 8;                      // 0, 8, 16, 24: row group of register r
-        if (trow / CH != part) continue;
-        stage_f[(trow % CH + row_l + (r & 3)) * EP_LD + j * 32 + col_l] = acc[i][j][r];
-      }
+  for (int ic = 0; ic < (MI16 ? TM : TM * (32 / CH)); ++ic) {
+    stage_round<MI16, TN, CH, EP_LD>(stage_f, acc, ic, lane);
     __builtin_amdgcn_s_waitcnt(WAIT_LGKM_ONLY);
 #pragma unroll 4
     for (int it = 0; it < CH / 4; ++it) {
       const int lr = it * 4 + vrow;
-      const int grow = row0 + i * 32 + part * CH + lr;
+      const int grow = row0 + ic * CH + lr;
       if (grow >= Mv || gcol >= p.N) continue;
-      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + lr * EP_LD + vcol);
+      const f32x4_t v4 = *reinterpret_cast<const f32x4_t*>(stage_f + stage_read_off<MI16, EP_LD>(it, vrow, vcol));
       float v[4] = {v4[0], v4[1], v4[2], v4[3]};
       if (Pz) {
         float* dst = Pz + (int64_t)grow * p.N + gcol;
@@ -729,6 +737,38 @@ __device__ __forceinline__ bf16x8_t pp_frag_at(const unsigned char* tile, uint32
   }
 }
 
+// The same for the 16x16x32 MFMA: a fragment is 16 rows x 32 reduction elements, lane l holds row l % 16 and the 8
+// elements 8 * (l / 16) .. + 7.  Reduction-contiguous tiles: logical chunk 4 * ks + l / 16 of the row for reduction
+// step ks (0 or 1) of a 64-wide tile, i.e. bit 6 of the byte offset flips with ks.  Strided tiles: the 16-lane group
+// g = l / 16 of a transposing read presents k-rows 8g .. 8g+3 (second read: + 4) x the fragment's 16 columns.
+template <bool KC>
+__device__ __forceinline__ uint32_t pp16_frag_base(int row0, int lane) {
+  if constexpr (KC) {
+    const int row = row0 + (lane & 15);
+    const int chunk0 = (lane >> 4) ^ (row & 7) ^ ((row >> 3) & 1);
+    return (uint32_t)(row * ROWB + (chunk0 << 4));
+  } else {
+    const int col = row0 + (lane & 3) * 4;                             // four columns this lane presents
+    const int kq = (lane & 15) >> 2;                                   // k & 3 of every row it reads
+    const int k0 = (lane >> 4) * 8 + kq;
+    const int cb = col * 2;
+    return (uint32_t)(k0 * 512 + (((cb >> 6) ^ kq) << 6) + (cb & 63));
+  }
+}
+template <bool KC>
+__device__ __forceinline__ bf16x8_t pp16_frag_at(const unsigned char* tile, uint32_t base, int ks) {
+  if constexpr (KC) {
+    return *reinterpret_cast<const bf16x8_t*>(tile + (base ^ (uint32_t)(ks << 6)));
+  } else {
+    union { s16x4_t h[2]; bf16x8_t v; } u;
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      u.h[q] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (lds_s16x4_t*)(lds_void_t*)(tile + base + ks * 16384 + q * 2048));
+    return u.v;
+  }
+}
+
 // The kernel is persistent: the grid is one block per CU, and each block walks its
 // list of (output tile, reduction split, batch) work items as ONE stream of
 // reduction tiles, so the loads of the next item's first tiles are in flight while
@@ -737,10 +777,19 @@ __device__ __forceinline__ bf16x8_t pp_frag_at(const unsigned char* tile, uint32
 constexpr int PP_EPI_OFF = 2 * PSTAGE;        // epilogue staging behind the two tile stages
 constexpr int PP_SMEM = PP_EPI_OFF + 8 * 4096;
 
-template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP>
+// MI16: the wave tile as 8 x 4 tiles of the 16x16x32 MFMA instead of 4 x 2 tiles of the 32x32x16 one.  Same LDS
+// layout, same number of fragment reads, twice as many (half as long) MFMAs.  On this part the 16x16x32 form
+// sustains an 11 % higher rate in a register-only loop on random operands (the clock is held by a power budget and
+// the smaller tile moves fewer accumulator bytes per flop); in the kernel it gains 4 % with both operands
+// reduction-contiguous and loses 2 % when one operand needs the transposing reads, so the launcher picks it for the
+// former only.
+template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP, bool MI16>
 __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_total) {
   constexpr int BM = 256, BN = 256, WGN = 4;
-  constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
+  constexpr int WM = 128, WN = 64;
+  constexpr int TM = MI16 ? 8 : 4, TN = MI16 ? 4 : 2;   // MFMA tiles per wave tile
+  constexpr int NF = MI16 ? 1 : 2;                      // reduction steps held in fragment registers at a time
+  using acc_t = typename std::conditional<MI16, f32x4_t, f32x16_t>::type;
   extern __shared__ __align__(1024) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -794,14 +843,14 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
 #pragma unroll
   for (int s = 1; s < kMaxSeg; ++s) nk_rest += (p.K[s] + BK - 1) / BK;
 
-  f32x16_t acc[TM][TN];
+  acc_t acc[TM][TN];
   auto zero_acc = [&]() {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int r = 0; r < (MI16 ? 4 : 16); ++r) acc[i][j][r] = 0.f;
   };
   zero_acc();
 
@@ -850,32 +899,45 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
     lb.load(make_rsrc(cB), ck_left, as + PTILE, wave);
     advance();
   };
-  bf16x8_t af[2][TM], bfr[2][TN];
+  bf16x8_t af[NF][TM], bfr[NF][TN];
   uint32_t abase[TM], bbase[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) abase[i] = pp_frag_base<AKC>(wm * WM + i * 32, lane);
+  for (int i = 0; i < TM; ++i)
+    abase[i] = MI16 ? pp16_frag_base<AKC>(wm * WM + i * 16, lane) : pp_frag_base<AKC>(wm * WM + i * 32, lane);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) bbase[j] = pp_frag_base<BKC>(wn * WN + j * 32, lane);
-  auto read_pair = [&](int stage, int kk0) {   // fragments of steps kk0, kk0+1
+  for (int j = 0; j < TN; ++j)
+    bbase[j] = MI16 ? pp16_frag_base<BKC>(wn * WN + j * 16, lane) : pp_frag_base<BKC>(wn * WN + j * 32, lane);
+  auto read_pair = [&](int stage, int kk0) {   // fragments of the 16-wide reduction steps kk0, kk0+1
     const unsigned char* as = smem + stage * PSTAGE;
     const unsigned char* bs = as + PTILE;
+    if constexpr (MI16) {                       // one 32-wide step; in the order the MFMAs consume them
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {   // in the order the MFMAs consume them
+      for (int j = 0; j < TN; ++j) bfr[0][j] = pp16_frag_at<BKC>(bs, bbase[j], kk0 >> 1);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag_at<BKC>(bs, bbase[j], kk0 + h);
+      for (int i = 0; i < TM; ++i) af[0][i] = pp16_frag_at<AKC>(as, abase[i], kk0 >> 1);
+    } else {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[h][i] = pp_frag_at<AKC>(as, abase[i], kk0 + h);
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[h][j] = pp_frag_at<BKC>(bs, bbase[j], kk0 + h);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[h][i] = pp_frag_at<AKC>(as, abase[i], kk0 + h);
+      }
     }
   };
-  auto mfma_pair = [&]() {   // 16 MFMAs from the fragment registers
+  auto mfma_pair = [&]() {   // the MFMAs of two 16-wide reduction steps from the fragment registers
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+    for (int h = 0; h < NF; ++h)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) {
+          if constexpr (MI16)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[h][i], bfr[h][j], acc[i][j], 0, 0, 0);
+        }
     __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -919,7 +981,7 @@ __global__ __launch_bounds__(512) void gemm_bf16_pp_kernel(GemmDev p, int work_t
       }
     }
     // item done: write it out while the next item's first tile is already in flight
-    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64>(p, Mv, acc, smem + PP_EPI_OFF + wave * 4096, lane,
+    gemm_epilogue<TM, TN, OUT_BF16, VEC, DROP, 16, 64, MI16>(p, Mv, acc, smem + PP_EPI_OFF + wave * 4096, lane,
                                                        it.m0 + wm * WM, it.n0 + wn * WN, it.batch, it.z);
     zero_acc();
   }
@@ -1213,7 +1275,7 @@ static hipError_t launch_one(const GemmDev& d, int batch, hipStream_t st) {
 template <bool AKC, bool BKC, bool OUT_BF16, bool VEC, bool DROP = false>
 static hipError_t launch_pp(const GemmDev& d, int batch, hipStream_t st) {
   constexpr int smem = PP_SMEM;
-  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16, VEC, DROP>;
+  auto kfn = gemm_bf16_pp_kernel<AKC, BKC, OUT_BF16, VEC, DROP, AKC && BKC>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
