@@ -121,6 +121,37 @@ def stream_ceilings(lib, torch, rows, V, e, iters=5):
     return out
 
 
+def vendor_gemm_reference(torch, inp, iters, workload):
+    """torch.matmul (the vendor BLAS) on the shapes of the three vocabulary products, random bf16 operands:
+    logits = h_c W_out^T, d_h_c = dlogits W_out, dW_out = dlogits^T h_c over the R non-pad rows."""
+    R, H, V = inp.n_nonpad(), inp.H, inp.V
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(1)
+    h = (torch.rand(R, H, device=dev, generator=g) - 0.5).bfloat16()
+    W = (torch.rand(V, H, device=dev, generator=g) - 0.5).bfloat16()
+    dz = (torch.rand(R, V, device=dev, generator=g) - 0.5).bfloat16()
+    outs = (torch.empty(R, V, device=dev, dtype=torch.bfloat16), torch.empty(R, H, device=dev, dtype=torch.bfloat16),
+            torch.empty(V, H, device=dev, dtype=torch.bfloat16))
+    prods = (("logits", lambda: torch.matmul(h, W.t(), out=outs[0])), ("d_h_c", lambda: torch.matmul(dz, W, out=outs[1])),
+             ("dW_out", lambda: torch.matmul(dz.t(), h, out=outs[2])))
+    res = {"workload": workload, "R": R, "H": H, "V": V, "flops_per_product": 2.0 * R * H * V,
+           "library": "torch.matmul (vendor BLAS), bf16 in, bf16 out", "iters": iters}
+    for name, fn in prods:
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        res[name] = {"ms": ms, "TFLOP/s": 2.0 * R * H * V / (ms * 1e-3) / 1e12,
+                     "frac_of_peak": 2.0 * R * H * V / (ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS}
+    return res
+
+
 def cpu_baseline(inp, budget_s: float = 40.0):
     """Oracle fwd+bwd on the first sentences of the batch, about `budget_s` seconds."""
     from oracle import attn_softmax_oracle as orc
@@ -278,6 +309,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy kernel (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--vendor-gemm-reference", action="store_true",
+                    help="only time the vendor BLAS (torch.matmul, bf16) on the three vocabulary products of the "
+                         "workload and exit: a yardstick for the hand-written kernels, never part of the path")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs the path on ONE GPU only (no collectives, no sharding); "
@@ -299,6 +333,10 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+        return
+
+    if a.vendor_gemm_reference:
+        print(json.dumps(vendor_gemm_reference(torch, make_inputs(a.workload, dtype=a.dtype), a.steps, a.workload)))
         return
 
     inp = make_inputs(a.workload, dtype=a.dtype)
